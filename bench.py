@@ -1,0 +1,217 @@
+#!/usr/bin/env python3
+"""Benchmark of the GRAWA distributed update on one MI355X.
+
+A "step" is one complete distributed phase for all K workers resident on the GPU: gradient
+norms -> weights -> center -> pull (with the local SGD step fused in where the configuration
+says so), i.e. one call of grawa_lgrawa_update / grawa_mgrawa_update[_sgd].  Inputs are
+synthetic, seeded, and already in HBM when the timed region starts.
+
+Prints ONE JSON line.  `value` is the update's HBM bandwidth under the minimum-traffic byte
+model (bytes every correct implementation must move: gradients read once for the norms,
+parameters read once and written once, gradients read a second time when the SGD step is
+fused) divided by the measured time per step.  `roofline` is the same kind of figure for the
+dominant kernel alone (center+pull), from HIP events recorded around that kernel inside the
+timed steps.  `cpu_baseline` is the float64 CPU reference timed on a bounded sample of the
+same workload on this machine's host cores.
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBPS = 8000.0
+
+
+def parse():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--config", type=int, default=2, help="benchmark configuration 0..4 (headline: 2)")
+    ap.add_argument("--variant", default=None, help="lgrawa | mgrawa (default: the configuration's)")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-sweep", action="store_true", help="do not also time the other configurations")
+    ap.add_argument("--cpu-seconds", type=float, default=15.0, help="target CPU time of the reference sample")
+    return ap.parse_args()
+
+
+def pick_variant(w, variant):
+    if variant:
+        return variant
+    return "lgrawa" if "lgrawa" in w.variants else w.variants[0]
+
+
+def call_update(plan, w, x, g, variant):
+    P = w.P
+    if variant == "lgrawa":
+        if w.fused_sgd:
+            plan.lgrawa_update_sgd(x[:, :P], g[:, :P], w.lam, g[:, :P], w.lr)
+        else:
+            plan.lgrawa_update(x[:, :P], g[:, :P], w.lam)
+    else:
+        if w.fused_sgd:
+            plan.mgrawa_update_sgd(x[:, :P], g[:, :P], w.lam, g[:, :P], w.lr)
+        else:
+            plan.mgrawa_update(x[:, :P], g[:, :P], w.lam)
+
+
+def time_config(torch, grawa, W, idx, variant, steps, warmup):
+    """Returns (stats dict, x, g, w) with x, g left on the device (x has been updated)."""
+    w = W.config(idx)
+    variant = pick_variant(w, variant)
+    x, g = W.make_inputs(w, device="cuda:0")
+    x0 = None
+    torch.cuda.synchronize()
+    with grawa.Plan(w.K, w.P, w.offsets) as plan:
+        info = plan.info()
+        for _ in range(warmup):
+            call_update(plan, w, x, g, variant)
+        torch.cuda.synchronize()
+        plan.profile(True)
+        t0 = time.perf_counter()
+        for _ in range(steps):
+            call_update(plan, w, x, g, variant)
+        torch.cuda.synchronize()
+        t1 = time.perf_counter()
+        prof = plan.profile_read()
+        plan.profile(False)
+    ms = (t1 - t0) * 1e3 / steps
+    model_bytes = w.update_bytes()
+    pull_bytes = w.K * w.P * (8 + (w.grad_bytes if w.fused_sgd else 0))
+    norm_bytes = w.K * w.P * w.grad_bytes
+    n = max(1, prof["calls"])
+    pull_ms = prof["pull_ms"] / n
+    norm_ms = prof["norm_ms"] / n
+    stats = {
+        "workload": w.name, "variant": variant + ("+sgd" if w.fused_sgd else ""), "K": w.K, "L": w.L, "P": w.P,
+        "grad_dtype": w.grad_dtype, "ms_per_step": ms, "updates_per_s": 1e3 / ms,
+        "model_bytes": model_bytes, "GBps": model_bytes / (ms * 1e-3) / 1e9,
+        "frac_of_peak": model_bytes / (ms * 1e-3) / 1e9 / HBM_PEAK_GBPS,
+        "norm_kernel_ms": norm_ms, "norm_kernel_GBps": norm_bytes / (norm_ms * 1e-3) / 1e9 if norm_ms > 0 else None,
+        "pull_kernel_ms": pull_ms, "pull_kernel_GBps": pull_bytes / (pull_ms * 1e-3) / 1e9 if pull_ms > 0 else None,
+        "pull_kernel_bytes": pull_bytes, "tile_elems": info["tile_elems"], "n_tiles": info["n_tiles"],
+    }
+    del x0
+    return stats, x, g, w
+
+
+def copy_ceiling(torch, grawa, nbytes=1 << 31, reps=10):
+    """Read+write bandwidth of a plain 128-bit copy kernel over nbytes (twice nbytes of traffic)."""
+    src = torch.empty(nbytes // 4, dtype=torch.float32, device="cuda:0").normal_()
+    dst = torch.empty_like(src)
+    for _ in range(2):
+        grawa.stream_copy(dst, src)
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    torch.cuda.synchronize()
+    e0.record()
+    for _ in range(reps):
+        grawa.stream_copy(dst, src)
+    e1.record()
+    torch.cuda.synchronize()
+    ms = e0.elapsed_time(e1) / reps
+    ok = bool(torch.equal(dst, src))
+    return {"GBps": 2 * nbytes / (ms * 1e-3) / 1e9, "ms": ms, "bytes_moved": 2 * nbytes, "verified": ok}
+
+
+def cpu_baseline(torch, W, w, variant, target_seconds):
+    """The float64 CPU reference, as it stands, on the first n columns of the same seeded
+    workload (all K workers, layers clipped to the sample); n is chosen from a short trial so
+    that the run takes about target_seconds.  One thread: the reference is plain sequential C."""
+    import numpy as np
+    from oracle import grawa_oracle as orc
+
+    x_dev, g_dev = W.make_inputs(w, device="cuda:0")
+
+    def run(n):
+        off = np.unique(np.clip(w.offsets, 0, n))
+        x = W.to_numpy_params(x_dev[:, :n].contiguous())
+        g = W.to_numpy_grads(g_dev[:, :n].contiguous())
+        t0 = time.perf_counter()
+        kw = dict(g_sgd=g, lr=w.lr) if w.fused_sgd else {}
+        if variant == "lgrawa":
+            orc.lgrawa_update(x, g, off, w.lam, **kw)
+        else:
+            orc.mgrawa_update(x, g, off, w.lam, **kw)
+        return time.perf_counter() - t0
+
+    n = min(w.P, 1 << 18)
+    t = run(n)
+    n_full = int(min(w.P, n * target_seconds / max(t, 1e-6)))
+    n_full -= n_full % 8
+    if n_full > n:
+        n, t = n_full, run(n_full)
+    del x_dev, g_dev
+    per = w.grad_bytes + 8 + (w.grad_bytes if w.fused_sgd else 0)
+    sample_bytes = w.K * n * per
+    return {
+        "value": sample_bytes / t / 1e9, "unit": "GB/s", "cores": 1, "kind": "oracle",
+        "sample": "first %d of %d columns of %s, all %d workers, layers clipped to the sample; %.1f s of CPU "
+                  "time; same byte model as value" % (n, w.P, w.name, w.K, t),
+        "seconds": t, "updates_per_s_extrapolated": 1.0 / (t * w.P / n), "host_cores_available": os.cpu_count(),
+    }
+
+
+def main():
+    a = parse()
+    if a.gpus != 1:
+        print("bench.py: this build runs the GRAWA update on ONE GPU (all K workers of a configuration "
+              "live on it); --gpus %d is not supported." % a.gpus, file=sys.stderr)
+        sys.exit(2)
+    import torch
+    from paper_2403_04206_amd import buildlib, grawa, workloads as W
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        sys.exit(2)
+    if not os.path.exists(grawa.LIB_PATH):
+        buildlib.build(force=True)
+
+    stats, x, g, w = time_config(torch, grawa, W, a.config, a.variant, a.steps, a.warmup)
+    del x, g
+    torch.cuda.empty_cache()
+    variant = pick_variant(w, a.variant)
+
+    roofline = {
+        "bound": "hbm", "kernel": "k_center_pull", "achieved": stats["pull_kernel_GBps"], "peak": HBM_PEAK_GBPS,
+        "unit": "GB/s", "frac": (stats["pull_kernel_GBps"] or 0.0) / HBM_PEAK_GBPS, "traffic": None,
+        "bytes_per_launch": stats["pull_kernel_bytes"], "avg_launch_ms": stats["pull_kernel_ms"],
+        "norm_kernel": {"achieved": stats["norm_kernel_GBps"], "avg_launch_ms": stats["norm_kernel_ms"],
+                        "frac": (stats["norm_kernel_GBps"] or 0.0) / HBM_PEAK_GBPS},
+    }
+    out = {
+        "metric": "grawa_update_hbm_bandwidth", "value": stats["GBps"], "unit": "GB/s", "n_gpus": 1,
+        "steps": a.steps, "warmup": a.warmup, "ms_per_step": stats["ms_per_step"], "higher_is_better": True,
+        "scaling": "weak", "vs_baseline": None, "dtype": "f32", "data": "synthetic",
+        "config": {"workload": w.name, "variant": stats["variant"], "K": w.K, "L": w.L, "P": w.P,
+                   "grad_dtype": w.grad_dtype, "lambda": w.lam, "bytes_per_update": stats["model_bytes"],
+                   "tile_elems": stats["tile_elems"]},
+        "frac_of_hbm_peak": stats["frac_of_peak"], "updates_per_s": stats["updates_per_s"],
+        "roofline": roofline,
+    }
+    out["copy_kernel"] = copy_ceiling(torch, grawa)
+    torch.cuda.empty_cache()
+    if not a.no_sweep:
+        sweep = []
+        for i in range(W.N_CONFIGS):
+            if i == a.config:
+                sweep.append({k: stats[k] for k in ("workload", "variant", "ms_per_step", "updates_per_s", "GBps",
+                                                     "frac_of_peak", "pull_kernel_GBps", "norm_kernel_GBps")})
+                continue
+            for var in W.config(i).variants:
+                s, x, g, _ = time_config(torch, grawa, W, i, var, a.steps, a.warmup)
+                del x, g
+                torch.cuda.empty_cache()
+                sweep.append({k: s[k] for k in ("workload", "variant", "ms_per_step", "updates_per_s", "GBps",
+                                                 "frac_of_peak", "pull_kernel_GBps", "norm_kernel_GBps")})
+        out["all_configs"] = sweep
+    if not a.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline(torch, W, w, variant, a.cpu_seconds)
+    print(json.dumps(out), flush=True)
+
+
+if __name__ == "__main__":
+    main()

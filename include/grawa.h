@@ -1,0 +1,188 @@
+/*
+ * grawa.h -- C ABI of the MI355X (gfx950) GRAWA distributed-update library.
+ *
+ * GRAWA (gradient-based weighted averaging) periodically pulls M data-parallel
+ * workers toward a center model that is a weighted average of the workers, the
+ * weights being inversely proportional to each worker's gradient norm.  This
+ * library computes one such distributed phase for all workers that live on one
+ * GPU, plus the local SGD step taken between phases.
+ *
+ * Notation.  K = number of workers (the paper's M); L = number of layers (the
+ * paper's K); P = parameters per worker.  Worker k's flat parameter vector is
+ * row k of x, its gradient is row k of g:
+ *     x : float  [K][ldx]   device, updated in place
+ *     g : float or bfloat16 [K][ldg]   device, never written
+ * Rows are contiguous, ld* >= P counts elements, columns >= P are never touched.
+ * A "layer" is any contiguous segment [offsets[l], offsets[l+1]) of the flat
+ * vector chosen by the caller (one parameter tensor, or a module).
+ *
+ * Conventions for every call below.
+ *  - All data pointers are DEVICE pointers unless the comment says "host".
+ *  - The caller owns every buffer it passes.  The library allocates device
+ *    memory only inside grawa_plan_create and frees it in grawa_plan_destroy.
+ *  - `stream` is a hipStream_t passed as void* (NULL = the default stream).
+ *    Calls enqueue their kernels on it and return without synchronising; two
+ *    calls that use the same plan must be ordered on one stream (the plan's
+ *    workspace is shared).
+ *  - Base pointers of x, g, center_out must be 16-byte aligned and ldx*4,
+ *    ldg*sizeof(g element) must be multiples of 16; otherwise
+ *    GRAWA_ERR_ALIGNMENT.  Layer offsets may be arbitrary.
+ *  - Arguments are validated before anything is launched: a call that returns an
+ *    error has launched nothing and changed nothing.
+ *  - No exception crosses this boundary; the return code is the only error
+ *    channel.  grawa_status_string turns it into text.
+ *  - Parameters are fp32.  Gradients are fp32 or bf16 (bf16 values are used as
+ *    stored, widened exactly).
+ */
+#ifndef GRAWA_H
+#define GRAWA_H
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    GRAWA_OK = 0,
+    GRAWA_ERR_INVALID_ARG = 1, /* null pointer, bad size, non-monotone offsets, lambda outside [0,1], non-finite scalar */
+    GRAWA_ERR_ALIGNMENT = 2,   /* base pointer or leading dimension not 16-byte aligned */
+    GRAWA_ERR_WORKSPACE = 3,   /* the plan could not get its device workspace */
+    GRAWA_ERR_UNSUPPORTED = 4, /* a size or dtype this build does not handle (K > GRAWA_MAX_WORKERS, ...) */
+    GRAWA_ERR_HIP = 5          /* a HIP runtime call or a kernel launch failed */
+} grawa_status_t;
+
+typedef enum { GRAWA_F32 = 0, GRAWA_BF16 = 1 } grawa_dtype_t;
+
+/* Which scalar score a worker gets in the model-level variants. */
+typedef enum {
+    GRAWA_NORM_LAYERSUM = 0, /* MGRAWA, Sec. 5.1 eq. (3): A_k = sum over layers of ||G_layer||_F  */
+    GRAWA_NORM_FLAT = 1      /* vanilla GRAWA, Sec. 4.3.1 eq. (2): A_k = ||flattened gradient||_2 */
+} grawa_norm_mode_t;
+
+#define GRAWA_MAX_WORKERS 1024
+
+typedef struct grawa_plan grawa_plan_t; /* opaque */
+
+/* Text for a status code (static storage, never NULL). */
+const char *grawa_status_string(grawa_status_t s);
+
+/*
+ * Plan: the shape of one problem (K workers, P parameters, L layers) and the
+ * device workspace for it -- the layer offsets, a map from fixed-size tiles of
+ * the flat vector to layers (no tile crosses a layer boundary), per-tile partial
+ * sums, and the K x L tables of squared norms, scores and weights.
+ *   out                 host pointer that receives the plan
+ *   layer_offsets_host  host array of L+1 values, [0] = 0, strictly increasing,
+ *                       [L] = P; may be NULL only when L == 1
+ * Uses the current HIP device; the plan must be used on that device.
+ * Errors: INVALID_ARG (K < 1, P < 1, L < 1, L > P, bad offsets, out NULL),
+ * UNSUPPORTED (K > GRAWA_MAX_WORKERS), WORKSPACE / HIP (allocation or copy failed).
+ */
+grawa_status_t grawa_plan_create(grawa_plan_t **out, int K, int64_t P, int L,
+                                 const int64_t *layer_offsets_host);
+
+/* Frees the plan and its workspace.  The caller must have synchronised the
+ * streams that used it.  NULL is accepted. */
+grawa_status_t grawa_plan_destroy(grawa_plan_t *plan);
+
+/*
+ * Gradient-norm scores, Sec. 5.2 eq. (5)-(6): norms_out[k][l] = ||g_k restricted
+ * to layer l||_F, the Frobenius norm of worker k's accumulated gradient in layer
+ * l.  Sums of squares are accumulated in fp32 per thread over at most 32
+ * elements and in fp64 from there on.  norms_out: device float [K][L].
+ */
+grawa_status_t grawa_grad_norms(grawa_plan_t *plan, const void *g, int64_t ldg,
+                                grawa_dtype_t g_dtype, float *norms_out, void *stream);
+
+/*
+ * One model-level distributed phase (Sec. 4.3.1 and Sec. 5.1, the body of the
+ * "if" in Algorithm 1):
+ *   A_k     score of worker k from g, per `mode` (eq. (3) or eq. (2))
+ *   beta_k  = (1/A_k) / sum_j (1/A_j)                            (eq. (4))
+ *   x_C     = sum_k beta_k x_k
+ *   x_k    <- (1 - lambda) x_k + lambda x_C   for every k, from the pre-pull x
+ * lambda must be finite and in [0, 1].  center_out (float [P]) receives x_C if
+ * not NULL; weights_out (float [K]) receives beta if not NULL.
+ * Zero scores: if any A_k is exactly 0 those workers share the weight equally
+ * and the rest get 0 (the limit A -> 0+); +inf gives weight 0; NaN propagates.
+ */
+grawa_status_t grawa_mgrawa_update(grawa_plan_t *plan, float *x, int64_t ldx, const void *g,
+                                   int64_t ldg, grawa_dtype_t g_dtype, grawa_norm_mode_t mode,
+                                   float lambda, float *center_out, float *weights_out,
+                                   void *stream);
+
+/*
+ * One layer-level distributed phase (Sec. 5.2 eqs. (5)-(7), the body of the
+ * "if" in Algorithm 2): as above, but every layer l has its own scores
+ * A_k^l = ||G_k^l||_F and its own weights beta_k^l normalised over the workers,
+ * and the center is the concatenation of the per-layer weighted averages.
+ * weights_out: float [K][L] or NULL.
+ */
+grawa_status_t grawa_lgrawa_update(grawa_plan_t *plan, float *x, int64_t ldx, const void *g,
+                                   int64_t ldg, grawa_dtype_t g_dtype, float lambda,
+                                   float *center_out, float *weights_out, void *stream);
+
+/*
+ * Center and pull with weights supplied by the caller (the display after eq. (2);
+ * eq. (7) when per_layer != 0).  weights: device float [K] (per_layer == 0) or
+ * [K][L] (per_layer != 0); they are used as given, not renormalised.
+ */
+grawa_status_t grawa_center_pull(grawa_plan_t *plan, float *x, int64_t ldx, const float *weights,
+                                 int per_layer, float lambda, float *center_out, void *stream);
+
+/*
+ * Local SGD step of Algorithms 1 and 2: x_k <- x_k - lr * g_k for every worker.
+ * Needs no plan.  lr must be finite.
+ */
+grawa_status_t grawa_local_sgd(float *x, int64_t ldx, const void *g, int64_t ldg,
+                               grawa_dtype_t g_dtype, int K, int64_t P, float lr, void *stream);
+
+/*
+ * Local SGD step fused into the distributed phase, in the order of Algorithms 1
+ * and 2 (SGD step first, then the phase):
+ *   x'_k = x_k - lr * gs_k ;  x_C = sum_k beta_k x'_k ;  x_k <- (1-lambda) x'_k + lambda x_C
+ * with beta from the scores of g (as in the calls above).  g_sgd may be the same
+ * array as g (the local-gradient variant of Appendix G) or a different one; it
+ * has the same dtype as g and its own leading dimension.
+ */
+grawa_status_t grawa_mgrawa_update_sgd(grawa_plan_t *plan, float *x, int64_t ldx, const void *g,
+                                       int64_t ldg, grawa_dtype_t g_dtype, grawa_norm_mode_t mode,
+                                       float lambda, const void *g_sgd, int64_t ldg_sgd, float lr,
+                                       float *center_out, float *weights_out, void *stream);
+
+grawa_status_t grawa_lgrawa_update_sgd(grawa_plan_t *plan, float *x, int64_t ldx, const void *g,
+                                       int64_t ldg, grawa_dtype_t g_dtype, float lambda,
+                                       const void *g_sgd, int64_t ldg_sgd, float lr,
+                                       float *center_out, float *weights_out, void *stream);
+
+/*
+ * Measurement aids (not part of the method).
+ *
+ * grawa_plan_profile: with enable != 0 the plan records a pair of HIP events
+ * around the gradient-norm kernel and around the center+pull kernel of every
+ * later update call (up to 4096 calls, then it stops recording).  With
+ * enable == 0 recording stops.  Either way the counters are reset.
+ *
+ * grawa_plan_profile_read: the caller must have synchronised the stream.
+ * Returns the number of recorded calls in *n_calls and the summed durations in
+ * milliseconds of the two kernels (host pointers; any may be NULL).
+ *
+ * grawa_stream_copy: dst[i] = src[i] for nbytes bytes (multiple of 16, both
+ * pointers 16-byte aligned) with the same 128-bit access pattern as the update
+ * kernels; a plain copy of known size used to calibrate hardware counters and
+ * to measure the attainable HBM bandwidth of the machine.
+ */
+grawa_status_t grawa_plan_profile(grawa_plan_t *plan, int enable);
+grawa_status_t grawa_plan_profile_read(grawa_plan_t *plan, int *n_calls, double *norm_ms,
+                                       double *pull_ms);
+grawa_status_t grawa_stream_copy(void *dst, const void *src, int64_t nbytes, void *stream);
+
+/* Number of tiles the plan cut the flat vector into, and the tile length in
+ * elements (host-side queries; for tests and the byte model). */
+grawa_status_t grawa_plan_info(const grawa_plan_t *plan, int64_t *n_tiles, int *tile_elems);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* GRAWA_H */

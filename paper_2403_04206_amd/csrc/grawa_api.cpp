@@ -1,0 +1,380 @@
+// Host side of the C ABI declared in include/grawa.h: argument checks, the plan (tile map
+// and workspace) and the launch sequence of each entry point.  Nothing here computes any
+// part of the update; every step runs in the kernels of grawa_kernels.hip.
+#include <cmath>
+#include <cstdlib>
+#include <cstring>
+#include <new>
+#include <vector>
+
+#include "grawa_internal.h"
+
+namespace {
+
+constexpr int kDefaultTileElems = 8192;
+
+inline bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+
+inline size_t round256(size_t n) { return (n + 255) & ~size_t(255); }
+
+int tile_elems_from_env()
+{
+    // Tuning knob: tile length in elements (multiple of 8, 256 .. 1048576).
+    const char *e = std::getenv("GRAWA_TILE_ELEMS");
+    if (!e || !*e) return kDefaultTileElems;
+    char *end = nullptr;
+    long v = std::strtol(e, &end, 10);
+    if (end == e || *end != '\0' || v < 256 || v > (1 << 20) || (v % 8) != 0) return kDefaultTileElems;
+    return (int)v;
+}
+
+grawa_status_t check_params(const grawa_plan *p, const float *x, int64_t ldx)
+{
+    if (!p || !x) return GRAWA_ERR_INVALID_ARG;
+    if (ldx < p->P) return GRAWA_ERR_INVALID_ARG;
+    if (!aligned16(x) || (ldx % 4) != 0) return GRAWA_ERR_ALIGNMENT;
+    return GRAWA_OK;
+}
+
+grawa_status_t check_grads(int64_t P, const void *g, int64_t ldg, grawa_dtype_t dt)
+{
+    if (!g) return GRAWA_ERR_INVALID_ARG;
+    if (dt != GRAWA_F32 && dt != GRAWA_BF16) return GRAWA_ERR_UNSUPPORTED;
+    if (ldg < P) return GRAWA_ERR_INVALID_ARG;
+    const int64_t per16 = (dt == GRAWA_BF16) ? 8 : 4;
+    if (!aligned16(g) || (ldg % per16) != 0) return GRAWA_ERR_ALIGNMENT;
+    return GRAWA_OK;
+}
+
+grawa_status_t check_lambda(float lambda)
+{
+    if (!std::isfinite(lambda) || lambda < 0.f || lambda > 1.f) return GRAWA_ERR_INVALID_ARG;
+    return GRAWA_OK;
+}
+
+grawa_status_t check_center(const float *c)
+{
+    if (c && !aligned16(c)) return GRAWA_ERR_ALIGNMENT;
+    return GRAWA_OK;
+}
+
+struct DeviceGuard { // the plan's kernels run on the device the plan was made on
+    int prev = -1;
+    bool ok = true;
+    explicit DeviceGuard(int dev)
+    {
+        if (hipGetDevice(&prev) != hipSuccess) { ok = false; return; }
+        if (prev != dev && hipSetDevice(dev) != hipSuccess) ok = false;
+    }
+    ~DeviceGuard()
+    {
+        int cur = -1;
+        if (prev >= 0 && hipGetDevice(&cur) == hipSuccess && cur != prev) (void)hipSetDevice(prev);
+    }
+};
+
+// Event pair bookkeeping for the measurement aid.
+inline bool prof_active(const grawa_plan *p) { return p->profile_on && p->profile_n < GRAWA_PROFILE_SLOTS; }
+
+#define GRAWA_TRY_HIP(expr)                       \
+    do {                                          \
+        if ((expr) != hipSuccess) return GRAWA_ERR_HIP; \
+    } while (0)
+
+// norms -> weights -> (sgd) center pull; shared by the four update entry points.
+grawa_status_t run_update(grawa_plan *p, float *x, int64_t ldx, const void *g, int64_t ldg,
+                          grawa_dtype_t dt, int per_layer, grawa_norm_mode_t mode, float lambda,
+                          const void *g_sgd, int64_t ldg_sgd, float lr, int fuse_sgd, float *center_out,
+                          float *weights_out, hipStream_t s)
+{
+    grawa_status_t st;
+    if ((st = check_params(p, x, ldx)) != GRAWA_OK) return st;
+    if ((st = check_grads(p->P, g, ldg, dt)) != GRAWA_OK) return st;
+    if ((st = check_lambda(lambda)) != GRAWA_OK) return st;
+    if ((st = check_center(center_out)) != GRAWA_OK) return st;
+    if (mode != GRAWA_NORM_LAYERSUM && mode != GRAWA_NORM_FLAT) return GRAWA_ERR_INVALID_ARG;
+    if (fuse_sgd) {
+        if ((st = check_grads(p->P, g_sgd, ldg_sgd, dt)) != GRAWA_OK) return st;
+        if (!std::isfinite(lr)) return GRAWA_ERR_INVALID_ARG;
+    }
+    DeviceGuard guard(p->device);
+    if (!guard.ok) return GRAWA_ERR_HIP;
+
+    const bool prof = prof_active(p);
+    hipEvent_t *ev = prof ? p->ev + 4 * (size_t)p->profile_n : nullptr;
+
+    if (prof) GRAWA_TRY_HIP(hipEventRecord(ev[0], s));
+    GRAWA_TRY_HIP(grawa_launch_sumsq(p, g, ldg, dt, s));
+    if (prof) GRAWA_TRY_HIP(hipEventRecord(ev[1], s));
+
+    GRAWA_TRY_HIP(grawa_launch_finalize_layers(p, nullptr, per_layer ? weights_out : nullptr, s));
+    if (!per_layer) GRAWA_TRY_HIP(grawa_launch_finalize_model(p, mode, weights_out, s));
+
+    if (prof) GRAWA_TRY_HIP(hipEventRecord(ev[2], s));
+    GRAWA_TRY_HIP(grawa_launch_center_pull(p, x, ldx, per_layer ? p->d_beta_layer : p->d_beta_model,
+                                           per_layer, lambda, g_sgd, ldg_sgd, dt, lr, fuse_sgd,
+                                           center_out, s));
+    if (prof) {
+        GRAWA_TRY_HIP(hipEventRecord(ev[3], s));
+        p->profile_n += 1;
+    }
+    return GRAWA_OK;
+}
+
+} // namespace
+
+extern "C" {
+
+const char *grawa_status_string(grawa_status_t s)
+{
+    switch (s) {
+    case GRAWA_OK: return "ok";
+    case GRAWA_ERR_INVALID_ARG: return "invalid argument";
+    case GRAWA_ERR_ALIGNMENT: return "pointer or leading dimension not 16-byte aligned";
+    case GRAWA_ERR_WORKSPACE: return "workspace allocation failed";
+    case GRAWA_ERR_UNSUPPORTED: return "unsupported size or dtype";
+    case GRAWA_ERR_HIP: return "HIP runtime error";
+    }
+    return "unknown status";
+}
+
+grawa_status_t grawa_plan_create(grawa_plan_t **out, int K, int64_t P, int L,
+                                 const int64_t *layer_offsets_host)
+{
+    if (!out) return GRAWA_ERR_INVALID_ARG;
+    *out = nullptr;
+    if (K < 1 || P < 1 || L < 1 || (int64_t)L > P) return GRAWA_ERR_INVALID_ARG;
+    if (!layer_offsets_host && L != 1) return GRAWA_ERR_INVALID_ARG;
+    if (K > GRAWA_MAX_WORKERS) return GRAWA_ERR_UNSUPPORTED;
+
+    std::vector<int64_t> off((size_t)L + 1);
+    if (layer_offsets_host) {
+        std::memcpy(off.data(), layer_offsets_host, sizeof(int64_t) * ((size_t)L + 1));
+    } else {
+        off[0] = 0;
+        off[1] = P;
+    }
+    if (off[0] != 0 || off[(size_t)L] != P) return GRAWA_ERR_INVALID_ARG;
+    for (int l = 0; l < L; ++l)
+        if (off[(size_t)l + 1] <= off[(size_t)l]) return GRAWA_ERR_INVALID_ARG;
+
+    // Tile map: cut every layer at the multiples of T of the flat index, so tile starts are
+    // either a multiple of T or a layer start and no tile crosses a layer boundary.
+    const int T = tile_elems_from_env();
+    std::vector<GrawaTile> tiles;
+    std::vector<int32_t> layer_tile0((size_t)L + 1);
+    const int64_t max_tiles = (int64_t)1 << 24; // keeps grid.x * 256 below 2^32
+    if (P / T + L > max_tiles) return GRAWA_ERR_UNSUPPORTED;
+    tiles.reserve((size_t)(P / T + L + 1));
+    for (int l = 0; l < L; ++l) {
+        layer_tile0[(size_t)l] = (int32_t)tiles.size();
+        int64_t s = off[(size_t)l];
+        const int64_t e = off[(size_t)l + 1];
+        while (s < e) {
+            int64_t stop = (s / T + 1) * T;
+            if (stop > e) stop = e;
+            tiles.push_back(GrawaTile{s, (int32_t)(stop - s), (int32_t)l});
+            s = stop;
+        }
+    }
+    layer_tile0[(size_t)L] = (int32_t)tiles.size();
+    const int64_t nt = (int64_t)tiles.size();
+
+    grawa_plan *p = new (std::nothrow) grawa_plan();
+    if (!p) return GRAWA_ERR_WORKSPACE;
+    std::memset(p, 0, sizeof(*p));
+    p->K = K;
+    p->L = L;
+    p->P = P;
+    p->tile_elems = T;
+    p->n_tiles = nt;
+    if (hipGetDevice(&p->device) != hipSuccess) {
+        delete p;
+        return GRAWA_ERR_HIP;
+    }
+
+    const size_t b_tiles = round256(sizeof(GrawaTile) * (size_t)nt);
+    const size_t b_lt0 = round256(sizeof(int32_t) * ((size_t)L + 1));
+    const size_t b_part = round256(sizeof(double) * (size_t)K * (size_t)nt);
+    const size_t b_S = round256(sizeof(double) * (size_t)K * (size_t)L);
+    const size_t b_A = round256(sizeof(float) * (size_t)K * (size_t)L);
+    const size_t b_bl = b_A;
+    const size_t b_bm = round256(sizeof(float) * (size_t)K);
+    p->ws_bytes = b_tiles + b_lt0 + b_part + b_S + b_A + b_bl + b_bm;
+    if (hipMalloc(&p->ws, p->ws_bytes) != hipSuccess) {
+        (void)hipGetLastError();
+        delete p;
+        return GRAWA_ERR_WORKSPACE;
+    }
+    char *w = static_cast<char *>(p->ws);
+    p->d_tiles = reinterpret_cast<GrawaTile *>(w); w += b_tiles;
+    p->d_layer_tile0 = reinterpret_cast<int32_t *>(w); w += b_lt0;
+    p->d_partials = reinterpret_cast<double *>(w); w += b_part;
+    p->d_S = reinterpret_cast<double *>(w); w += b_S;
+    p->d_A = reinterpret_cast<float *>(w); w += b_A;
+    p->d_beta_layer = reinterpret_cast<float *>(w); w += b_bl;
+    p->d_beta_model = reinterpret_cast<float *>(w);
+
+    if (hipMemcpy(p->d_tiles, tiles.data(), sizeof(GrawaTile) * (size_t)nt, hipMemcpyHostToDevice) != hipSuccess ||
+        hipMemcpy(p->d_layer_tile0, layer_tile0.data(), sizeof(int32_t) * ((size_t)L + 1), hipMemcpyHostToDevice) != hipSuccess ||
+        hipMemset(p->d_partials, 0, b_part + b_S + b_A + b_bl + b_bm) != hipSuccess) {
+        (void)hipFree(p->ws);
+        delete p;
+        return GRAWA_ERR_HIP;
+    }
+    *out = p;
+    return GRAWA_OK;
+}
+
+grawa_status_t grawa_plan_destroy(grawa_plan_t *p)
+{
+    if (!p) return GRAWA_OK;
+    grawa_status_t st = GRAWA_OK;
+    if (p->ev) {
+        for (int i = 0; i < 4 * GRAWA_PROFILE_SLOTS; ++i)
+            if (p->ev[i]) (void)hipEventDestroy(p->ev[i]);
+        delete[] p->ev;
+    }
+    if (p->ws && hipFree(p->ws) != hipSuccess) st = GRAWA_ERR_HIP;
+    delete p;
+    return st;
+}
+
+grawa_status_t grawa_plan_info(const grawa_plan_t *p, int64_t *n_tiles, int *tile_elems)
+{
+    if (!p) return GRAWA_ERR_INVALID_ARG;
+    if (n_tiles) *n_tiles = p->n_tiles;
+    if (tile_elems) *tile_elems = p->tile_elems;
+    return GRAWA_OK;
+}
+
+grawa_status_t grawa_grad_norms(grawa_plan_t *p, const void *g, int64_t ldg, grawa_dtype_t dt,
+                                float *norms_out, void *stream)
+{
+    if (!p || !norms_out) return GRAWA_ERR_INVALID_ARG;
+    grawa_status_t st = check_grads(p->P, g, ldg, dt);
+    if (st != GRAWA_OK) return st;
+    DeviceGuard guard(p->device);
+    if (!guard.ok) return GRAWA_ERR_HIP;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    GRAWA_TRY_HIP(grawa_launch_sumsq(p, g, ldg, dt, s));
+    GRAWA_TRY_HIP(grawa_launch_finalize_layers(p, norms_out, nullptr, s));
+    return GRAWA_OK;
+}
+
+grawa_status_t grawa_mgrawa_update(grawa_plan_t *p, float *x, int64_t ldx, const void *g, int64_t ldg,
+                                   grawa_dtype_t dt, grawa_norm_mode_t mode, float lambda,
+                                   float *center_out, float *weights_out, void *stream)
+{
+    return run_update(p, x, ldx, g, ldg, dt, 0, mode, lambda, nullptr, 0, 0.f, 0, center_out, weights_out,
+                      static_cast<hipStream_t>(stream));
+}
+
+grawa_status_t grawa_lgrawa_update(grawa_plan_t *p, float *x, int64_t ldx, const void *g, int64_t ldg,
+                                   grawa_dtype_t dt, float lambda, float *center_out, float *weights_out,
+                                   void *stream)
+{
+    return run_update(p, x, ldx, g, ldg, dt, 1, GRAWA_NORM_LAYERSUM, lambda, nullptr, 0, 0.f, 0, center_out,
+                      weights_out, static_cast<hipStream_t>(stream));
+}
+
+grawa_status_t grawa_mgrawa_update_sgd(grawa_plan_t *p, float *x, int64_t ldx, const void *g, int64_t ldg,
+                                       grawa_dtype_t dt, grawa_norm_mode_t mode, float lambda,
+                                       const void *g_sgd, int64_t ldg_sgd, float lr, float *center_out,
+                                       float *weights_out, void *stream)
+{
+    return run_update(p, x, ldx, g, ldg, dt, 0, mode, lambda, g_sgd, ldg_sgd, lr, 1, center_out, weights_out,
+                      static_cast<hipStream_t>(stream));
+}
+
+grawa_status_t grawa_lgrawa_update_sgd(grawa_plan_t *p, float *x, int64_t ldx, const void *g, int64_t ldg,
+                                       grawa_dtype_t dt, float lambda, const void *g_sgd, int64_t ldg_sgd,
+                                       float lr, float *center_out, float *weights_out, void *stream)
+{
+    return run_update(p, x, ldx, g, ldg, dt, 1, GRAWA_NORM_LAYERSUM, lambda, g_sgd, ldg_sgd, lr, 1, center_out,
+                      weights_out, static_cast<hipStream_t>(stream));
+}
+
+grawa_status_t grawa_center_pull(grawa_plan_t *p, float *x, int64_t ldx, const float *weights, int per_layer,
+                                 float lambda, float *center_out, void *stream)
+{
+    grawa_status_t st;
+    if ((st = check_params(p, x, ldx)) != GRAWA_OK) return st;
+    if (!weights) return GRAWA_ERR_INVALID_ARG;
+    if ((st = check_lambda(lambda)) != GRAWA_OK) return st;
+    if ((st = check_center(center_out)) != GRAWA_OK) return st;
+    DeviceGuard guard(p->device);
+    if (!guard.ok) return GRAWA_ERR_HIP;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    const bool prof = prof_active(p);
+    hipEvent_t *ev = prof ? p->ev + 4 * (size_t)p->profile_n : nullptr;
+    if (prof) {
+        GRAWA_TRY_HIP(hipEventRecord(ev[0], s));
+        GRAWA_TRY_HIP(hipEventRecord(ev[1], s));
+        GRAWA_TRY_HIP(hipEventRecord(ev[2], s));
+    }
+    GRAWA_TRY_HIP(grawa_launch_center_pull(p, x, ldx, weights, per_layer ? 1 : 0, lambda, nullptr, 0, GRAWA_F32,
+                                           0.f, 0, center_out, s));
+    if (prof) {
+        GRAWA_TRY_HIP(hipEventRecord(ev[3], s));
+        p->profile_n += 1;
+    }
+    return GRAWA_OK;
+}
+
+grawa_status_t grawa_local_sgd(float *x, int64_t ldx, const void *g, int64_t ldg, grawa_dtype_t dt, int K,
+                               int64_t P, float lr, void *stream)
+{
+    if (!x || K < 1 || P < 1 || ldx < P) return GRAWA_ERR_INVALID_ARG;
+    if (K > 65535 || P > ((int64_t)1 << 35)) return GRAWA_ERR_UNSUPPORTED;
+    if (!aligned16(x) || (ldx % 4) != 0) return GRAWA_ERR_ALIGNMENT;
+    grawa_status_t st = check_grads(P, g, ldg, dt);
+    if (st != GRAWA_OK) return st;
+    if (!std::isfinite(lr)) return GRAWA_ERR_INVALID_ARG;
+    GRAWA_TRY_HIP(grawa_launch_local_sgd(x, ldx, g, ldg, dt, K, P, lr, static_cast<hipStream_t>(stream)));
+    return GRAWA_OK;
+}
+
+grawa_status_t grawa_plan_profile(grawa_plan_t *p, int enable)
+{
+    if (!p) return GRAWA_ERR_INVALID_ARG;
+    DeviceGuard guard(p->device);
+    if (!guard.ok) return GRAWA_ERR_HIP;
+    if (enable && !p->ev) {
+        p->ev = new (std::nothrow) hipEvent_t[4 * GRAWA_PROFILE_SLOTS]();
+        if (!p->ev) return GRAWA_ERR_WORKSPACE;
+        for (int i = 0; i < 4 * GRAWA_PROFILE_SLOTS; ++i)
+            if (hipEventCreate(&p->ev[i]) != hipSuccess) return GRAWA_ERR_HIP;
+    }
+    p->profile_on = enable ? 1 : 0;
+    p->profile_n = 0;
+    return GRAWA_OK;
+}
+
+grawa_status_t grawa_plan_profile_read(grawa_plan_t *p, int *n_calls, double *norm_ms, double *pull_ms)
+{
+    if (!p) return GRAWA_ERR_INVALID_ARG;
+    double a = 0.0, b = 0.0;
+    for (int i = 0; i < p->profile_n; ++i) {
+        float ms = 0.f;
+        GRAWA_TRY_HIP(hipEventElapsedTime(&ms, p->ev[4 * i + 0], p->ev[4 * i + 1]));
+        a += ms;
+        GRAWA_TRY_HIP(hipEventElapsedTime(&ms, p->ev[4 * i + 2], p->ev[4 * i + 3]));
+        b += ms;
+    }
+    if (n_calls) *n_calls = p->profile_n;
+    if (norm_ms) *norm_ms = a;
+    if (pull_ms) *pull_ms = b;
+    return GRAWA_OK;
+}
+
+grawa_status_t grawa_stream_copy(void *dst, const void *src, int64_t nbytes, void *stream)
+{
+    if (!dst || !src || nbytes < 0) return GRAWA_ERR_INVALID_ARG;
+    if (!aligned16(dst) || !aligned16(src) || (nbytes % 16) != 0) return GRAWA_ERR_ALIGNMENT;
+    if (nbytes / 16 > ((int64_t)1 << 34)) return GRAWA_ERR_UNSUPPORTED;
+    GRAWA_TRY_HIP(grawa_launch_stream_copy(dst, src, nbytes, static_cast<hipStream_t>(stream)));
+    return GRAWA_OK;
+}
+
+} // extern "C"

@@ -1,0 +1,59 @@
+// Internal declarations shared by the host API (grawa_api.cpp) and the kernel
+// translation unit (grawa_kernels.hip).  Not installed; the public ABI is include/grawa.h.
+#ifndef GRAWA_INTERNAL_H
+#define GRAWA_INTERNAL_H
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "grawa.h"
+
+// One tile of the flat parameter vector.  A tile never crosses a layer boundary, so one
+// weight per worker serves the whole tile.  16 bytes: fetched with one scalar load.
+struct GrawaTile {
+    int64_t start; // first element (index into a row)
+    int32_t len;   // 1 .. tile_elems
+    int32_t layer; // layer the tile lies in
+};
+
+#define GRAWA_PROFILE_SLOTS 4096
+
+struct grawa_plan {
+    int K;
+    int L;
+    int64_t P;
+    int tile_elems;
+    int64_t n_tiles;
+    int device;
+    // one device allocation, carved up:
+    void *ws;
+    size_t ws_bytes;
+    GrawaTile *d_tiles;     // [n_tiles]
+    int32_t *d_layer_tile0; // [L+1] first tile of every layer
+    double *d_partials;     // [K][n_tiles] per-tile sums of squares
+    double *d_S;            // [K][L] squared Frobenius norms
+    float *d_A;             // [K][L] layer norms
+    float *d_beta_layer;    // [K][L] per-layer weights
+    float *d_beta_model;    // [K] model-level weights
+    // measurement aid
+    int profile_on;
+    int profile_n;
+    hipEvent_t *ev; // 4 per slot: norm begin/end, pull begin/end
+};
+
+// Launchers (defined in grawa_kernels.hip).  All return the hipError_t of the launch.
+hipError_t grawa_launch_sumsq(const grawa_plan *p, const void *g, int64_t ldg, grawa_dtype_t dt,
+                              hipStream_t s);
+hipError_t grawa_launch_finalize_layers(const grawa_plan *p, float *norms_user, float *beta_user,
+                                        hipStream_t s);
+hipError_t grawa_launch_finalize_model(const grawa_plan *p, grawa_norm_mode_t mode, float *beta_user,
+                                       hipStream_t s);
+hipError_t grawa_launch_center_pull(const grawa_plan *p, float *x, int64_t ldx, const float *beta,
+                                    int per_layer, float lambda, const void *g_sgd,
+                                    int64_t ldg_sgd, grawa_dtype_t dt, float lr, int fuse_sgd,
+                                    float *center_out, hipStream_t s);
+hipError_t grawa_launch_local_sgd(float *x, int64_t ldx, const void *g, int64_t ldg,
+                                  grawa_dtype_t dt, int K, int64_t P, float lr, hipStream_t s);
+hipError_t grawa_launch_stream_copy(void *dst, const void *src, int64_t nbytes, hipStream_t s);
+
+#endif

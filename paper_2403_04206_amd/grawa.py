@@ -1,0 +1,224 @@
+"""ctypes binding of libgrawa.so: the same names and arguments as include/grawa.h.
+
+Argument marshalling only -- every step of the update runs in the library's HIP
+kernels.  Tensors are torch CUDA tensors used purely as device memory: the binding
+passes ``data_ptr()``, the row stride and the current stream's handle.  There is no
+CPU path: if the library has not been built, or a call fails, an exception is raised.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+
+import numpy as np
+import torch
+
+_PKG = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_PKG, "libgrawa.so")
+
+OK, ERR_INVALID_ARG, ERR_ALIGNMENT, ERR_WORKSPACE, ERR_UNSUPPORTED, ERR_HIP = range(6)
+F32, BF16 = 0, 1
+NORM_LAYERSUM, NORM_FLAT = 0, 1
+MAX_WORKERS = 1024
+
+_NORM_MODES = {"layersum": NORM_LAYERSUM, "flat": NORM_FLAT, NORM_LAYERSUM: NORM_LAYERSUM, NORM_FLAT: NORM_FLAT}
+
+
+class GrawaError(RuntimeError):
+    def __init__(self, status: int, where: str):
+        self.status = int(status)
+        super().__init__("%s failed: %s (status %d)" % (where, status_string(status), status))
+
+
+_lib = None
+
+
+def lib():
+    """Load libgrawa.so (once).  Raises if it is not built -- there is no fallback."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(LIB_PATH):
+        raise RuntimeError(
+            "%s is missing: build it first (python -m paper_2403_04206_amd.buildlib, "
+            "or __graft_entry__.build())" % LIB_PATH)
+    L = C.CDLL(LIB_PATH)
+    vp, i64, it, fl, dbl = C.c_void_p, C.c_int64, C.c_int, C.c_float, C.c_double
+    sig = {
+        "grawa_status_string": (C.c_char_p, [it]),
+        "grawa_plan_create": (it, [C.POINTER(vp), it, i64, it, vp]),
+        "grawa_plan_destroy": (it, [vp]),
+        "grawa_plan_info": (it, [vp, C.POINTER(i64), C.POINTER(it)]),
+        "grawa_grad_norms": (it, [vp, vp, i64, it, vp, vp]),
+        "grawa_mgrawa_update": (it, [vp, vp, i64, vp, i64, it, it, fl, vp, vp, vp]),
+        "grawa_lgrawa_update": (it, [vp, vp, i64, vp, i64, it, fl, vp, vp, vp]),
+        "grawa_center_pull": (it, [vp, vp, i64, vp, it, fl, vp, vp]),
+        "grawa_local_sgd": (it, [vp, i64, vp, i64, it, it, i64, fl, vp]),
+        "grawa_mgrawa_update_sgd": (it, [vp, vp, i64, vp, i64, it, it, fl, vp, i64, fl, vp, vp, vp]),
+        "grawa_lgrawa_update_sgd": (it, [vp, vp, i64, vp, i64, it, fl, vp, i64, fl, vp, vp, vp]),
+        "grawa_plan_profile": (it, [vp, it]),
+        "grawa_plan_profile_read": (it, [vp, C.POINTER(it), C.POINTER(dbl), C.POINTER(dbl)]),
+        "grawa_stream_copy": (it, [vp, vp, i64, vp]),
+    }
+    for name, (res, args) in sig.items():
+        fn = getattr(L, name)
+        fn.restype = res
+        fn.argtypes = args
+    _lib = L
+    return L
+
+
+def status_string(status: int) -> str:
+    return lib().grawa_status_string(int(status)).decode()
+
+
+def _check(status: int, where: str):
+    if status != OK:
+        raise GrawaError(status, where)
+
+
+def _stream(stream=None):
+    if stream is None:
+        stream = torch.cuda.current_stream()
+    return C.c_void_p(stream.cuda_stream if hasattr(stream, "cuda_stream") else int(stream))
+
+
+def _ptr(t):
+    return C.c_void_p(0 if t is None else t.data_ptr())
+
+
+def _params(x: torch.Tensor):
+    if x.dtype != torch.float32 or x.dim() != 2 or x.stride(1) != 1 or not x.is_cuda:
+        raise TypeError("x must be a float32 CUDA tensor [K, P] with unit column stride")
+    return x.data_ptr(), x.stride(0)
+
+
+def _grads(g: torch.Tensor):
+    if g.dim() != 2 or g.stride(1) != 1 or not g.is_cuda:
+        raise TypeError("g must be a CUDA tensor [K, P] with unit column stride")
+    if g.dtype == torch.float32:
+        return g.data_ptr(), g.stride(0), F32
+    if g.dtype == torch.bfloat16:
+        return g.data_ptr(), g.stride(0), BF16
+    raise TypeError("g must be float32 or bfloat16")
+
+
+class Plan:
+    """grawa_plan_t: problem shape, tile map and device workspace (see include/grawa.h)."""
+
+    def __init__(self, K: int, P: int, layer_offsets=None):
+        if layer_offsets is None:
+            L = 1
+            off_p = None
+            self._off = None
+        else:
+            self._off = np.ascontiguousarray(layer_offsets, dtype=np.int64)
+            L = self._off.size - 1
+            off_p = self._off.ctypes.data_as(C.c_void_p)
+        self.K, self.P, self.L = int(K), int(P), int(L)
+        self._h = C.c_void_p()
+        _check(lib().grawa_plan_create(C.byref(self._h), self.K, self.P, self.L, off_p), "grawa_plan_create")
+
+    # -- lifetime -------------------------------------------------------------------
+    def destroy(self):
+        if getattr(self, "_h", None) is not None and self._h.value:
+            torch.cuda.synchronize()
+            st = lib().grawa_plan_destroy(self._h)
+            self._h = C.c_void_p()
+            _check(st, "grawa_plan_destroy")
+
+    def __del__(self):
+        try:
+            self.destroy()
+        except Exception:
+            pass
+
+    def __enter__(self):
+        return self
+
+    def __exit__(self, *exc):
+        self.destroy()
+
+    def info(self):
+        n, t = C.c_int64(), C.c_int()
+        _check(lib().grawa_plan_info(self._h, C.byref(n), C.byref(t)), "grawa_plan_info")
+        return {"n_tiles": n.value, "tile_elems": t.value}
+
+    # -- the calls ------------------------------------------------------------------
+    def grad_norms(self, g, norms_out=None, stream=None):
+        gp, ldg, dt = _grads(g)
+        if norms_out is None:
+            norms_out = torch.empty((self.K, self.L), dtype=torch.float32, device=g.device)
+        _check(lib().grawa_grad_norms(self._h, gp, ldg, dt, _ptr(norms_out), _stream(stream)), "grawa_grad_norms")
+        return norms_out
+
+    def mgrawa_update(self, x, g, lam, mode="layersum", center_out=None, weights_out=None, stream=None):
+        xp, ldx = _params(x)
+        gp, ldg, dt = _grads(g)
+        _check(lib().grawa_mgrawa_update(self._h, xp, ldx, gp, ldg, dt, _NORM_MODES[mode], float(lam),
+                                         _ptr(center_out), _ptr(weights_out), _stream(stream)),
+               "grawa_mgrawa_update")
+
+    def lgrawa_update(self, x, g, lam, center_out=None, weights_out=None, stream=None):
+        xp, ldx = _params(x)
+        gp, ldg, dt = _grads(g)
+        _check(lib().grawa_lgrawa_update(self._h, xp, ldx, gp, ldg, dt, float(lam), _ptr(center_out),
+                                         _ptr(weights_out), _stream(stream)), "grawa_lgrawa_update")
+
+    def mgrawa_update_sgd(self, x, g, lam, g_sgd, lr, mode="layersum", center_out=None, weights_out=None,
+                          stream=None):
+        xp, ldx = _params(x)
+        gp, ldg, dt = _grads(g)
+        sp, lds, dts = _grads(g_sgd)
+        if dts != dt:
+            raise TypeError("g and g_sgd must have the same dtype")
+        _check(lib().grawa_mgrawa_update_sgd(self._h, xp, ldx, gp, ldg, dt, _NORM_MODES[mode], float(lam), sp, lds,
+                                             float(lr), _ptr(center_out), _ptr(weights_out), _stream(stream)),
+               "grawa_mgrawa_update_sgd")
+
+    def lgrawa_update_sgd(self, x, g, lam, g_sgd, lr, center_out=None, weights_out=None, stream=None):
+        xp, ldx = _params(x)
+        gp, ldg, dt = _grads(g)
+        sp, lds, dts = _grads(g_sgd)
+        if dts != dt:
+            raise TypeError("g and g_sgd must have the same dtype")
+        _check(lib().grawa_lgrawa_update_sgd(self._h, xp, ldx, gp, ldg, dt, float(lam), sp, lds, float(lr),
+                                             _ptr(center_out), _ptr(weights_out), _stream(stream)),
+               "grawa_lgrawa_update_sgd")
+
+    def center_pull(self, x, weights, lam, center_out=None, stream=None):
+        xp, ldx = _params(x)
+        if weights.dtype != torch.float32 or not weights.is_contiguous():
+            raise TypeError("weights must be a contiguous float32 tensor [K] or [K, L]")
+        per_layer = 1 if weights.dim() == 2 else 0
+        want = (self.K, self.L) if per_layer else (self.K,)
+        if tuple(weights.shape) != want:
+            raise ValueError("weights must have shape %r" % (want,))
+        _check(lib().grawa_center_pull(self._h, xp, ldx, _ptr(weights), per_layer, float(lam), _ptr(center_out),
+                                       _stream(stream)), "grawa_center_pull")
+
+    # -- measurement aid ------------------------------------------------------------
+    def profile(self, enable: bool):
+        _check(lib().grawa_plan_profile(self._h, 1 if enable else 0), "grawa_plan_profile")
+
+    def profile_read(self):
+        n, a, b = C.c_int(), C.c_double(), C.c_double()
+        _check(lib().grawa_plan_profile_read(self._h, C.byref(n), C.byref(a), C.byref(b)), "grawa_plan_profile_read")
+        return {"calls": n.value, "norm_ms": a.value, "pull_ms": b.value}
+
+
+def local_sgd(x, g, lr, P=None, stream=None):
+    """grawa_local_sgd: x[k] -= lr * g[k] on the first P columns of every row."""
+    xp, ldx = _params(x)
+    gp, ldg, dt = _grads(g)
+    K = x.shape[0]
+    P = x.shape[1] if P is None else int(P)
+    _check(lib().grawa_local_sgd(xp, ldx, gp, ldg, dt, K, P, float(lr), _stream(stream)), "grawa_local_sgd")
+
+
+def stream_copy(dst, src, stream=None):
+    """grawa_stream_copy over two equally sized contiguous tensors."""
+    nbytes = src.numel() * src.element_size()
+    if dst.numel() * dst.element_size() != nbytes:
+        raise ValueError("size mismatch")
+    _check(lib().grawa_stream_copy(_ptr(dst), _ptr(src), nbytes, _stream(stream)), "grawa_stream_copy")

@@ -1,0 +1,254 @@
+"""GPU parity: the HIP library, called through its C ABI, against the float64 CPU reference
+element by element on the same seeded inputs.  Sizes here are ones the reference finishes in
+seconds; they span several tiles, ragged tails, unaligned layer offsets and every worker-count
+branch of the center+pull kernel."""
+import numpy as np
+import pytest
+import torch
+
+from oracle import grawa_oracle as orc
+from paper_2403_04206_amd import grawa, workloads as W
+from parity_util import TIGHT, assert_params_close, assert_table_close, operand_scale, tol_for
+
+pytestmark = pytest.mark.gpu
+DEV = "cuda:0"
+
+
+def say(msg):
+    print("[case] " + msg, flush=True)
+
+
+def host(x, g):
+    return W.to_numpy_params(x), W.to_numpy_grads(g)
+
+
+def run_variant(w, x, g, variant, lam, fused=False, lr=0.0, want_center=True, want_weights=True):
+    """Run one update on the GPU (in place on a clone) and in the reference; compare everything."""
+    P, K, L = w.P, w.K, w.L
+    xh, gh = host(x, g)
+    xg = x.clone()
+    per_layer = variant == "lgrawa"
+    mode = "flat" if variant == "flat" else "layersum"
+    cen = torch.full((W.round_up(P, 4),), float("nan"), device=DEV) if want_center else None
+    wts = torch.full((K, L) if per_layer else (K,), float("nan"), device=DEV) if want_weights else None
+    with grawa.Plan(K, P, w.offsets) as plan:
+        xv = xg[:, :P]
+        if per_layer:
+            if fused:
+                plan.lgrawa_update_sgd(xv, g[:, :P], lam, g[:, :P], lr, center_out=cen, weights_out=wts)
+            else:
+                plan.lgrawa_update(xv, g[:, :P], lam, center_out=cen, weights_out=wts)
+        else:
+            if fused:
+                plan.mgrawa_update_sgd(xv, g[:, :P], lam, g[:, :P], lr, mode=mode, center_out=cen, weights_out=wts)
+            else:
+                plan.mgrawa_update(xv, g[:, :P], lam, mode=mode, center_out=cen, weights_out=wts)
+        torch.cuda.synchronize()
+    kw = dict(g_sgd=gh, lr=lr) if fused else {}
+    ref = orc.lgrawa_update(xh, gh, w.offsets, lam, **kw) if per_layer else orc.mgrawa_update(xh, gh, w.offsets, lam, mode, **kw)
+    tol = tol_for(w.grad_dtype)
+    what = "%s/%s%s" % (w.name, variant, "+sgd" if fused else "")
+    got = xg.cpu().numpy()
+    sc = operand_scale(xh[:, :P], gh if fused else None, lr)
+    worst = assert_params_close(got[:, :P], ref["x"], w.offsets, min(tol, TIGHT), what + " x", sc)
+    if want_center:
+        assert_params_close(cen.cpu().numpy()[:P], ref["center"], w.offsets, min(tol, TIGHT), what + " center", sc)
+    if want_weights:
+        assert_table_close(wts.cpu().numpy(), ref["beta"], min(tol, TIGHT), what + " beta")
+    # padding columns (ld > P) are never written
+    np.testing.assert_array_equal(got[:, P:], xh[:, P:])
+    return worst
+
+
+# ----------------------------------------------------------------------------
+# configuration 0 (ResNet-20-shaped, K = 4), both layer readings, all variants
+# ----------------------------------------------------------------------------
+
+@pytest.mark.parametrize("grouped", [True, False])
+@pytest.mark.parametrize("variant", ["mgrawa", "flat", "lgrawa"])
+def test_config0(grouped, variant):
+    w = W.config(0)
+    if not grouped:
+        w = W.Workload("cfg0_resnet20_59tensors", 4, W.resnet20_layers(False), lam=0.1, seed=(0, 0))
+    say("config0 grouped=%s variant=%s K=%d L=%d P=%d" % (grouped, variant, w.K, w.L, w.P))
+    x, g = W.make_inputs(w, device=DEV)
+    run_variant(w, x, g, variant, w.lam)
+
+
+# ----------------------------------------------------------------------------
+# adversarial layouts
+# ----------------------------------------------------------------------------
+
+RAGGED = [1, 3, 8193, 2, 5, 8191, 20000, 7, 1, 1, 4096, 33, 16385, 6]     # crosses tiles, unaligned everywhere
+SMALL = [5, 1, 33, 8, 130]
+
+
+@pytest.mark.parametrize("K", [1, 2, 3, 4, 5, 8, 9, 16, 17, 32, 33, 40])
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_worker_counts_ragged(K, dtype):
+    sizes = RAGGED if K <= 17 else RAGGED[:8]
+    w, x, g = W.make_small(100 + K, K, sizes, grad_dtype=dtype, ld_pad=8, device=DEV)
+    say("ragged K=%d dtype=%s P=%d" % (K, dtype, w.P))
+    for variant in ("mgrawa", "lgrawa"):
+        run_variant(w, x, g, variant, 0.3)
+    run_variant(w, x, g, "lgrawa", 0.25, fused=True, lr=0.1)
+    run_variant(w, x, g, "flat", 0.7, fused=True, lr=0.05, want_center=False, want_weights=False)
+
+
+@pytest.mark.parametrize("sizes", [[1], [2], [3], [4], [5], [7, 1], [1, 1, 1, 1, 1], [8192], [8193], [8191, 1, 8192],
+                                   [16384, 3], SMALL])
+def test_tiny_and_boundary_layouts(sizes):
+    for dtype in ("f32", "bf16"):
+        w, x, g = W.make_small(7, 3, sizes, grad_dtype=dtype, device=DEV)
+        say("layout sizes=%r dtype=%s" % (sizes, dtype))
+        run_variant(w, x, g, "lgrawa", 0.5)
+        run_variant(w, x, g, "mgrawa", 0.5, fused=True, lr=0.2)
+
+
+def test_grad_norms_table():
+    for dtype in ("f32", "bf16"):
+        w, x, g = W.make_small(11, 6, RAGGED + [50000, 12], grad_dtype=dtype, ld_pad=16, device=DEV)
+        say("grad_norms dtype=%s P=%d" % (dtype, w.P))
+        with grawa.Plan(w.K, w.P, w.offsets) as plan:
+            A = plan.grad_norms(g[:, :w.P])
+            torch.cuda.synchronize()
+            info = plan.info()
+        assert info["n_tiles"] >= w.L
+        ref = orc.layer_norms(orc.grad_sumsq(W.to_numpy_grads(g), w.offsets))
+        worst = assert_table_close(A.cpu().numpy(), ref, TIGHT, "norms " + dtype)
+        assert worst < 2e-6      # fp32 chains of <= 32 squares, fp64 above: far inside the tolerance
+
+
+def test_local_sgd():
+    for dtype in ("f32", "bf16"):
+        for P in (1, 3, 4, 5, 1023, 4096, 4097, 70001):
+            K = 3
+            w, x, g = W.make_small(P, K, [P], grad_dtype=dtype, ld_pad=8, device=DEV)
+            say("local_sgd dtype=%s P=%d" % (dtype, P))
+            xh, gh = host(x, g)
+            xg = x.clone()
+            grawa.local_sgd(xg[:, :P], g[:, :P], 0.1)
+            torch.cuda.synchronize()
+            ref = orc.local_sgd(xh, gh, 0.1, P=P)
+            got = xg.cpu().numpy()
+            assert_params_close(got[:, :P], ref, [0, P], TIGHT, "local_sgd", operand_scale(xh[:, :P], gh, 0.1))
+            np.testing.assert_array_equal(got[:, P:], xh[:, P:])
+
+
+def test_center_pull_with_given_weights():
+    w, x, g = W.make_small(21, 5, RAGGED, device=DEV)
+    say("center_pull given weights")
+    rng = np.random.default_rng(0)
+    xh, _ = host(x, g)
+    for per_layer in (False, True):
+        b = rng.uniform(0.0, 1.0, size=(w.K, w.L) if per_layer else (w.K,)).astype(np.float32)
+        xg = x.clone()
+        cen = torch.empty(W.round_up(w.P, 4), device=DEV)
+        with grawa.Plan(w.K, w.P, w.offsets) as plan:
+            plan.center_pull(xg[:, :w.P], torch.from_numpy(b).to(DEV), 0.4, center_out=cen)
+            torch.cuda.synchronize()
+        ref_x, ref_c = orc.center_pull(xh, b.astype(np.float64), w.offsets, 0.4)
+        sc = operand_scale(xh[:, :w.P])
+        assert_params_close(xg.cpu().numpy()[:, :w.P], ref_x, w.offsets, TIGHT, "center_pull x", sc)
+        assert_params_close(cen.cpu().numpy()[:w.P], ref_c, w.offsets, TIGHT, "center_pull c", sc)
+
+
+def test_zero_norm_rule_on_device():
+    w, x, g = W.make_small(31, 4, [40, 9000, 17, 64], device=DEV)
+    say("zero-norm rule")
+    off = w.offsets
+    g[1:, off[0]:off[1]] = 0      # layer 0: only worker 0 has a gradient -> the other three share it
+    g[:, off[2]:off[3]] = 0       # layer 2: frozen for everybody -> plain average
+    g[2, :] = 0                   # worker 2: zero everywhere -> takes all the model-level weight
+    for variant in ("lgrawa", "mgrawa", "flat"):
+        run_variant(w, x, g, variant, 0.5)
+    wts = torch.empty((4, 4), device=DEV)
+    with grawa.Plan(w.K, w.P, off) as plan:
+        plan.lgrawa_update(x.clone()[:, :w.P], g[:, :w.P], 0.5, weights_out=wts)
+        torch.cuda.synchronize()
+    b = wts.cpu().numpy()
+    np.testing.assert_array_equal(b[:, 0], np.float32([0, 1 / 3, 1 / 3, 1 / 3]))
+    np.testing.assert_array_equal(b[:, 2], np.float32([0.25] * 4))
+    np.testing.assert_array_equal(b[:, 1], np.float32([0, 0, 1, 0]))
+
+
+def test_exact_special_cases():
+    say("K=1 / lambda=0 / lambda=1")
+    # K = 1: the worker is left bit-for-bit unchanged
+    w, x, g = W.make_small(41, 1, RAGGED, device=DEV)
+    xg = x.clone()
+    with grawa.Plan(1, w.P, w.offsets) as plan:
+        plan.lgrawa_update(xg[:, :w.P], g[:, :w.P], 0.37)
+        plan.mgrawa_update(xg[:, :w.P], g[:, :w.P], 0.9)
+        torch.cuda.synchronize()
+    assert torch.equal(xg, x)
+    # lambda = 0: identity for any K; lambda = 1: every worker lands on the center
+    w, x, g = W.make_small(42, 6, RAGGED, device=DEV)
+    xg = x.clone()
+    cen = torch.empty(W.round_up(w.P, 4), device=DEV)
+    with grawa.Plan(6, w.P, w.offsets) as plan:
+        plan.lgrawa_update(xg[:, :w.P], g[:, :w.P], 0.0)
+        torch.cuda.synchronize()
+        assert torch.equal(xg, x)
+        plan.lgrawa_update(xg[:, :w.P], g[:, :w.P], 1.0, center_out=cen)
+        torch.cuda.synchronize()
+    spread = (xg[:, :w.P] - cen[:w.P]).abs().max().item()
+    assert spread <= 1e-6 * x[:, :w.P].abs().max().item()
+
+
+def test_errors_launch_nothing():
+    say("error paths")
+    w, x, g = W.make_small(51, 4, SMALL + [64], device=DEV)
+    P = w.P
+    x0 = x.clone()
+    with grawa.Plan(4, P, w.offsets) as plan:
+        for lam in (-0.1, 1.5, float("nan"), float("inf")):
+            with pytest.raises(grawa.GrawaError) as e:
+                plan.lgrawa_update(x[:, :P], g[:, :P], lam)
+            assert e.value.status == grawa.ERR_INVALID_ARG
+        ld = x.stride(0)
+        buf = torch.zeros(4 * ld + 4, device=DEV)
+        with pytest.raises(grawa.GrawaError) as e:                      # base pointer 4 bytes off
+            plan.lgrawa_update(buf[1:1 + 4 * ld].view(4, ld)[:, :P], g[:, :P], 0.1)
+        assert e.value.status == grawa.ERR_ALIGNMENT
+        with pytest.raises(grawa.GrawaError) as e:                      # row stride not a multiple of 16 bytes
+            plan.lgrawa_update(torch.zeros((4, ld + 2), device=DEV)[:, :P], g[:, :P], 0.1)
+        assert e.value.status == grawa.ERR_ALIGNMENT
+        short = torch.empty((4, W.round_up(P, 8) - 8), device=DEV)       # ld < P
+        with pytest.raises(grawa.GrawaError) as e:
+            plan.lgrawa_update(short, g[:, :P], 0.1)
+        assert e.value.status == grawa.ERR_INVALID_ARG
+        with pytest.raises(grawa.GrawaError) as e:
+            plan.lgrawa_update_sgd(x[:, :P], g[:, :P], 0.1, g[:, :P], float("nan"))
+        assert e.value.status == grawa.ERR_INVALID_ARG
+        torch.cuda.synchronize()
+    assert torch.equal(x, x0)
+
+
+def test_repeated_calls_reuse_the_plan():
+    # the workspace carries nothing from one call to the next
+    w, x, g = W.make_small(61, 8, RAGGED, device=DEV)
+    say("plan reuse")
+    w2, x2, g2 = W.make_small(62, 8, RAGGED, device=DEV)
+    xh2, gh2 = host(x2, g2)
+    with grawa.Plan(8, w.P, w.offsets) as plan:
+        plan.lgrawa_update(x[:, :w.P], g[:, :w.P], 0.2)
+        plan.mgrawa_update(x[:, :w.P], g[:, :w.P], 0.2)
+        plan.lgrawa_update(x2[:, :w.P], g2[:, :w.P], 0.2)
+        torch.cuda.synchronize()
+    ref = orc.lgrawa_update(xh2, gh2, w.offsets, 0.2)
+    assert_params_close(x2.cpu().numpy()[:, :w.P], ref["x"], w.offsets, TIGHT, "reuse", operand_scale(xh2[:, :w.P]))
+
+
+def test_side_stream():
+    w, x, g = W.make_small(71, 4, RAGGED, device=DEV)
+    say("side stream")
+    xh, gh = host(x, g)
+    s = torch.cuda.Stream()
+    torch.cuda.synchronize()
+    with grawa.Plan(4, w.P, w.offsets) as plan:
+        with torch.cuda.stream(s):
+            plan.lgrawa_update(x[:, :w.P], g[:, :w.P], 0.2)
+        s.synchronize()
+    ref = orc.lgrawa_update(xh, gh, w.offsets, 0.2)
+    assert_params_close(x.cpu().numpy()[:, :w.P], ref["x"], w.offsets, TIGHT, "side stream", operand_scale(xh[:, :w.P]))
