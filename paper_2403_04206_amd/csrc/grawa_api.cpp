@@ -180,6 +180,21 @@ grawa_status_t grawa_plan_create(grawa_plan_t **out, int K, int64_t P, int L,
     layer_tile0[(size_t)L] = (int32_t)tiles.size();
     const int64_t nt = (int64_t)tiles.size();
 
+    // Cell map of the center+pull pass: block m covers columns [256 m, 256 m + 256).
+    const int64_t cell = 256;
+    const int64_t nc = (P + cell - 1) / cell;
+    if (nc >= max_tiles) return GRAWA_ERR_UNSUPPORTED;
+    std::vector<int32_t> cell_layer((size_t)nc);
+    {
+        int l = 0;
+        for (int64_t m = 0; m < nc; ++m) {
+            const int64_t first = m * cell;
+            const int64_t last = (first + cell < P ? first + cell : P) - 1;
+            while (off[(size_t)l + 1] <= first) ++l;
+            cell_layer[(size_t)m] = (off[(size_t)l + 1] > last) ? (int32_t)l : ~(int32_t)l;
+        }
+    }
+
     grawa_plan *p = new (std::nothrow) grawa_plan();
     if (!p) return GRAWA_ERR_WORKSPACE;
     std::memset(p, 0, sizeof(*p));
@@ -188,11 +203,14 @@ grawa_status_t grawa_plan_create(grawa_plan_t **out, int K, int64_t P, int L,
     p->P = P;
     p->tile_elems = T;
     p->n_tiles = nt;
+    p->n_cells = nc;
     if (hipGetDevice(&p->device) != hipSuccess) {
         delete p;
         return GRAWA_ERR_HIP;
     }
 
+    const size_t b_off = round256(sizeof(int64_t) * ((size_t)L + 1));
+    const size_t b_cells = round256(sizeof(int32_t) * (size_t)nc);
     const size_t b_tiles = round256(sizeof(GrawaTile) * (size_t)nt);
     const size_t b_lt0 = round256(sizeof(int32_t) * ((size_t)L + 1));
     const size_t b_part = round256(sizeof(double) * (size_t)K * (size_t)nt);
@@ -200,13 +218,15 @@ grawa_status_t grawa_plan_create(grawa_plan_t **out, int K, int64_t P, int L,
     const size_t b_A = round256(sizeof(float) * (size_t)K * (size_t)L);
     const size_t b_bl = b_A;
     const size_t b_bm = round256(sizeof(float) * (size_t)K);
-    p->ws_bytes = b_tiles + b_lt0 + b_part + b_S + b_A + b_bl + b_bm;
+    p->ws_bytes = b_off + b_cells + b_tiles + b_lt0 + b_part + b_S + b_A + b_bl + b_bm;
     if (hipMalloc(&p->ws, p->ws_bytes) != hipSuccess) {
         (void)hipGetLastError();
         delete p;
         return GRAWA_ERR_WORKSPACE;
     }
     char *w = static_cast<char *>(p->ws);
+    p->d_off = reinterpret_cast<int64_t *>(w); w += b_off;
+    p->d_cell_layer = reinterpret_cast<int32_t *>(w); w += b_cells;
     p->d_tiles = reinterpret_cast<GrawaTile *>(w); w += b_tiles;
     p->d_layer_tile0 = reinterpret_cast<int32_t *>(w); w += b_lt0;
     p->d_partials = reinterpret_cast<double *>(w); w += b_part;
@@ -215,7 +235,9 @@ grawa_status_t grawa_plan_create(grawa_plan_t **out, int K, int64_t P, int L,
     p->d_beta_layer = reinterpret_cast<float *>(w); w += b_bl;
     p->d_beta_model = reinterpret_cast<float *>(w);
 
-    if (hipMemcpy(p->d_tiles, tiles.data(), sizeof(GrawaTile) * (size_t)nt, hipMemcpyHostToDevice) != hipSuccess ||
+    if (hipMemcpy(p->d_off, off.data(), sizeof(int64_t) * ((size_t)L + 1), hipMemcpyHostToDevice) != hipSuccess ||
+        hipMemcpy(p->d_cell_layer, cell_layer.data(), sizeof(int32_t) * (size_t)nc, hipMemcpyHostToDevice) != hipSuccess ||
+        hipMemcpy(p->d_tiles, tiles.data(), sizeof(GrawaTile) * (size_t)nt, hipMemcpyHostToDevice) != hipSuccess ||
         hipMemcpy(p->d_layer_tile0, layer_tile0.data(), sizeof(int32_t) * ((size_t)L + 1), hipMemcpyHostToDevice) != hipSuccess ||
         hipMemset(p->d_partials, 0, b_part + b_S + b_A + b_bl + b_bm) != hipSuccess) {
         (void)hipFree(p->ws);
@@ -326,7 +348,7 @@ grawa_status_t grawa_local_sgd(float *x, int64_t ldx, const void *g, int64_t ldg
                                int64_t P, float lr, void *stream)
 {
     if (!x || K < 1 || P < 1 || ldx < P) return GRAWA_ERR_INVALID_ARG;
-    if (K > 65535 || P > ((int64_t)1 << 35)) return GRAWA_ERR_UNSUPPORTED;
+    if (K > 65535 || P >= ((int64_t)1 << 32)) return GRAWA_ERR_UNSUPPORTED;
     if (!aligned16(x) || (ldx % 4) != 0) return GRAWA_ERR_ALIGNMENT;
     grawa_status_t st = check_grads(P, g, ldg, dt);
     if (st != GRAWA_OK) return st;

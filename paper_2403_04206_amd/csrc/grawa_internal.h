@@ -8,8 +8,8 @@
 
 #include "grawa.h"
 
-// One tile of the flat parameter vector.  A tile never crosses a layer boundary, so one
-// weight per worker serves the whole tile.  16 bytes: fetched with one scalar load.
+// One tile of the flat vector for the norm pass.  A tile never crosses a layer boundary, so
+// its sum of squares belongs to one layer.  16 bytes: fetched with one scalar load.
 struct GrawaTile {
     int64_t start; // first element (index into a row)
     int32_t len;   // 1 .. tile_elems
@@ -24,12 +24,15 @@ struct grawa_plan {
     int64_t P;
     int tile_elems;
     int64_t n_tiles;
+    int64_t n_cells; // ceil(P / 256): blocks of the center+pull pass
     int device;
     // one device allocation, carved up:
     void *ws;
     size_t ws_bytes;
+    int64_t *d_off;         // [L+1] layer offsets
     GrawaTile *d_tiles;     // [n_tiles]
     int32_t *d_layer_tile0; // [L+1] first tile of every layer
+    int32_t *d_cell_layer;  // [n_cells] layer of a 256-column cell, or ~(first layer) if it holds a boundary
     double *d_partials;     // [K][n_tiles] per-tile sums of squares
     double *d_S;            // [K][L] squared Frobenius norms
     float *d_A;             // [K][L] layer norms

@@ -1,9 +1,15 @@
 // HIP kernels of the GRAWA distributed update for gfx950 (MI355X), wave64.
 //
 // The update is a streaming computation: every parameter and gradient element is read
-// once per pass and there is no reuse, so each kernel is built around 128-bit global
-// loads/stores, many of them in flight per lane, and nothing else.  There is no dense
-// contraction here and therefore no matrix-core code.
+// once per pass and there is no reuse, so each kernel is nothing but global loads and
+// stores kept in flight.  There is no dense contraction here and therefore no matrix-core
+// code.  Two measured facts shape the kernels:
+//   * read-only streams (the norm pass) run fastest with 128-bit non-temporal loads, several
+//     per lane;
+//   * the read-modify-write pass over K far-apart rows runs fastest when a wave touches one
+//     aligned 256-byte piece of every row (one 32-bit element per lane per row) and the
+//     blocks are small and many, again with non-temporal accesses -- provided every row
+//     starts on a 128-byte boundary, so that no cache line is written in two parts.
 //
 //   k_sumsq            per (tile, worker) sum of squares of the gradient   [eq. (3), (5)]
 //   k_finalize_layers  per layer: tile partials -> ||G||_F^2, ||G||_F, per-layer weights
@@ -81,31 +87,49 @@ __device__ __forceinline__ double block_min(double v, double *sm)
     return t;
 }
 
-// Gradient element access.  VEC16 = elements per 16-byte load (norm pass); a "quad" is 4
-// consecutive elements (what one lane handles next to one float4 of parameters).
+typedef float v4f __attribute__((ext_vector_type(4)));
+typedef unsigned int v4u __attribute__((ext_vector_type(4)));
+
+// Scalar (one element per lane) loads and stores, streaming (non-temporal) or plain.
+template <bool NT> __device__ __forceinline__ float ld_f32(const float *p)
+{
+    return NT ? __builtin_nontemporal_load(p) : *p;
+}
+template <bool NT> __device__ __forceinline__ void st_f32(float *p, float v)
+{
+    if (NT) __builtin_nontemporal_store(v, p);
+    else *p = v;
+}
+
+// Gradient element access.  VEC16 = elements per 16-byte load (norm pass).
 template <typename GT> struct Grad;
 
 template <> struct Grad<float> {
     static constexpr int VEC16 = 4;
     static __device__ __forceinline__ float one(const float *p) { return *p; }
+    template <bool NT> static __device__ __forceinline__ float ld(const float *p) { return ld_f32<NT>(p); }
+    // acc + sum of squares of the 4 floats at p (16-byte aligned), streaming load
     static __device__ __forceinline__ float sumsq16(const float *p, float acc)
     {
-        const float4 q = *reinterpret_cast<const float4 *>(p);
+        const v4f q = __builtin_nontemporal_load(reinterpret_cast<const v4f *>(p));
         acc = fmaf(q.x, q.x, acc);
         acc = fmaf(q.y, q.y, acc);
         acc = fmaf(q.z, q.z, acc);
         acc = fmaf(q.w, q.w, acc);
         return acc;
     }
-    static __device__ __forceinline__ float4 quad(const float *p) { return *reinterpret_cast<const float4 *>(p); }
 };
 
 template <> struct Grad<uint16_t> { // bfloat16 bit patterns
     static constexpr int VEC16 = 8;
     static __device__ __forceinline__ float one(const uint16_t *p) { return bf16_one(*p); }
+    template <bool NT> static __device__ __forceinline__ float ld(const uint16_t *p)
+    {
+        return bf16_one(NT ? __builtin_nontemporal_load(p) : *p);
+    }
     static __device__ __forceinline__ float sumsq16(const uint16_t *p, float acc)
     {
-        const uint4 q = *reinterpret_cast<const uint4 *>(p);
+        const v4u q = __builtin_nontemporal_load(reinterpret_cast<const v4u *>(p));
         float a;
         a = bf16_lo(q.x); acc = fmaf(a, a, acc);
         a = bf16_hi(q.x); acc = fmaf(a, a, acc);
@@ -117,11 +141,6 @@ template <> struct Grad<uint16_t> { // bfloat16 bit patterns
         a = bf16_hi(q.w); acc = fmaf(a, a, acc);
         return acc;
     }
-    static __device__ __forceinline__ float4 quad(const uint16_t *p)
-    {
-        const uint2 q = *reinterpret_cast<const uint2 *>(p);
-        return make_float4(bf16_lo(q.x), bf16_hi(q.x), bf16_lo(q.y), bf16_hi(q.y));
-    }
 };
 
 // ---------------------------------------------------------------------------------
@@ -129,9 +148,10 @@ template <> struct Grad<uint16_t> { // bfloat16 bit patterns
 // ---------------------------------------------------------------------------------
 
 // grid (n_tiles, K), block 256.  partials[k][tile] = sum over the tile of g[k][i]^2.
-// Each lane keeps 4 independent fp32 accumulators (one per load of an unrolled group of
-// four 16-byte loads), so a chain is at most tile_elems/256/4 elements long; everything
-// after the lane is fp64.
+// Each lane issues up to 8 independent 16-byte streaming loads per trip and keeps one fp32
+// accumulator per load, so an accumulator chain is at most tile_elems/256/8 vectors long
+// (one vector for the default tile); everything after the lane is fp64.
+#define GRAWA_SUMSQ_U 8
 template <typename GT>
 __global__ __launch_bounds__(GRAWA_BLOCK) void k_sumsq(const GT *__restrict__ g, int64_t ldg,
                                                        const GrawaTile *__restrict__ tiles,
@@ -150,33 +170,34 @@ __global__ __launch_bounds__(GRAWA_BLOCK) void k_sumsq(const GT *__restrict__ g,
     int64_t b_al = b / V * V;
     if (b_al < a_al) b_al = a_al;
 
-    float acc0 = 0.f, acc1 = 0.f, acc2 = 0.f, acc3 = 0.f;
+    float acc[GRAWA_SUMSQ_U];
+#pragma unroll
+    for (int u = 0; u < GRAWA_SUMSQ_U; ++u) acc[u] = 0.f;
 
     // unaligned head (< V elements) on the first lanes, tail on the lanes of the second wave
     if (tid < (int)(a_al - a)) {
         const float v = Grad<GT>::one(row + a + tid);
-        acc0 = v * v;
+        acc[0] = v * v;
     }
     if (tid >= GRAWA_WAVE && tid - GRAWA_WAVE < (int)(b - b_al)) {
         const float v = Grad<GT>::one(row + b_al + (tid - GRAWA_WAVE));
-        acc1 = v * v;
+        acc[1] = v * v;
     }
 
     const int nvec = (int)((b_al - a_al) / V);
     const GT *body = row + a_al;
-    int j = tid;
-    for (; j + 3 * GRAWA_BLOCK < nvec; j += 4 * GRAWA_BLOCK) {
-        acc0 = Grad<GT>::sumsq16(body + (int64_t)j * V, acc0);
-        acc1 = Grad<GT>::sumsq16(body + (int64_t)(j + GRAWA_BLOCK) * V, acc1);
-        acc2 = Grad<GT>::sumsq16(body + (int64_t)(j + 2 * GRAWA_BLOCK) * V, acc2);
-        acc3 = Grad<GT>::sumsq16(body + (int64_t)(j + 3 * GRAWA_BLOCK) * V, acc3);
+    for (int j0 = tid; j0 < nvec; j0 += GRAWA_SUMSQ_U * GRAWA_BLOCK) {
+#pragma unroll
+        for (int u = 0; u < GRAWA_SUMSQ_U; ++u) {
+            const int j = j0 + u * GRAWA_BLOCK;
+            if (j < nvec) acc[u] = Grad<GT>::sumsq16(body + (int64_t)j * V, acc[u]);
+        }
     }
-    if (j < nvec) acc0 = Grad<GT>::sumsq16(body + (int64_t)j * V, acc0);
-    if (j + GRAWA_BLOCK < nvec) acc1 = Grad<GT>::sumsq16(body + (int64_t)(j + GRAWA_BLOCK) * V, acc1);
-    if (j + 2 * GRAWA_BLOCK < nvec) acc2 = Grad<GT>::sumsq16(body + (int64_t)(j + 2 * GRAWA_BLOCK) * V, acc2);
 
     __shared__ double sm[GRAWA_BLOCK / GRAWA_WAVE];
-    const double lane = ((double)acc0 + (double)acc1) + ((double)acc2 + (double)acc3);
+    double lane = 0.0;
+#pragma unroll
+    for (int u = 0; u < GRAWA_SUMSQ_U; ++u) lane += (double)acc[u];
     const double total = block_sum(lane, sm);
     if (tid == 0) partials[(int64_t)k * n_tiles + blockIdx.x] = total;
 }
@@ -277,102 +298,68 @@ __global__ __launch_bounds__(GRAWA_BLOCK) void k_finalize_model(const double *__
 // center + pull (+ SGD on the way in)
 // ---------------------------------------------------------------------------------
 
-__device__ __forceinline__ float4 axpy4(float a, float4 g, float4 x)
-{ // x - a*g, one fma per component
-    return make_float4(fmaf(-a, g.x, x.x), fmaf(-a, g.y, x.y), fmaf(-a, g.z, x.z), fmaf(-a, g.w, x.w));
+#define GRAWA_CELL 256 // columns per block of the center+pull pass (one per lane)
+
+// Layer of column i, given a layer at or before it (cells that contain a layer boundary).
+__device__ __forceinline__ int layer_of(const int64_t *__restrict__ off, int layer, int L, int64_t i)
+{
+    while (layer + 1 < L && off[layer + 1] <= i) ++layer;
+    return layer;
 }
 
-// grid n_tiles, block 256.  KT = compile-time bound on the number of workers (K <= KT),
-// U = float4 columns a lane handles per trip.  A lane loads its column of all K workers
-// into registers (K*U independent 16-byte loads in flight), forms the weighted sum, and
-// writes the K pulled values back: every parameter is read once and written once.
+// grid ceil(P/256), block 256.  Lane t of block m owns column i = 256 m + t: it loads
+// x[k][i] for all K workers (K independent loads in flight; with SGD also g[k][i] and applies
+// x - lr g), forms c = sum_k beta_k x_k and writes x_k + lambda (c - x_k) back, so every
+// parameter is read once and written once.  A wave touches one 256-byte piece per row.
+// KT = compile-time bound on K.  NT = streaming loads/stores, chosen by the host only when
+// every row starts on a 128-byte boundary.
+// cell_layer[m] >= 0: the whole block lies in that layer (weights come through scalar
+// loads); < 0: the block contains a layer boundary, ~cell_layer[m] is the layer of its first
+// column and each lane finds its own layer.  Model-level weights pass cell_layer = nullptr.
 // The pull is x + lambda (c - x), one fma, which leaves a single worker exactly unchanged.
-template <int KT, int U, bool SGD, typename GT>
-__global__ __launch_bounds__(GRAWA_BLOCK) void k_center_pull(
+template <int KT, bool SGD, typename GT, bool NT>
+__global__ __launch_bounds__(GRAWA_CELL) void k_center_pull(
     float *__restrict__ x, int64_t ldx, const GT *__restrict__ g, int64_t ldg, float lr,
-    const float *__restrict__ beta, int64_t beta_stride, int per_layer,
-    const GrawaTile *__restrict__ tiles, int K, float lambda, float *__restrict__ center_out)
+    const float *__restrict__ beta, int64_t beta_stride, const int32_t *__restrict__ cell_layer,
+    const int64_t *__restrict__ off, int L, int K, int64_t P, float lambda,
+    float *__restrict__ center_out)
 {
-    const GrawaTile t = tiles[blockIdx.x];
-    const int tid = threadIdx.x;
-    const int bcol = per_layer ? t.layer : 0;
+    const int64_t i = (int64_t)blockIdx.x * GRAWA_CELL + threadIdx.x;
+    const bool ok = i < P;
+    float *xi = x + i;
 
-    float bk[KT];
+    float v[KT];
+    if (ok) {
 #pragma unroll
-    for (int k = 0; k < KT; ++k) bk[k] = (k < K) ? beta[(int64_t)k * beta_stride + bcol] : 0.f;
-
-    const int64_t a = t.start, b = t.start + t.len;
-    int64_t a_al = (a + 3) / 4 * 4;
-    if (a_al > b) a_al = b;
-    int64_t b_al = b / 4 * 4;
-    if (b_al < a_al) b_al = a_al;
-
-    // elements before / after the 16-byte aligned body: one lane each, two sweeps over k
-    {
-        int64_t i = -1;
-        if (tid < (int)(a_al - a)) i = a + tid;
-        else if (tid >= GRAWA_WAVE && tid - GRAWA_WAVE < (int)(b - b_al)) i = b_al + (tid - GRAWA_WAVE);
-        if (i >= 0) {
-            float c = 0.f;
-            for (int k = 0; k < K; ++k) {
-                float v = x[(int64_t)k * ldx + i];
-                if (SGD) v = fmaf(-lr, Grad<GT>::one(g + (int64_t)k * ldg + i), v);
-                c = fmaf(beta[(int64_t)k * beta_stride + bcol], v, c);
-            }
-            for (int k = 0; k < K; ++k) {
-                float v = x[(int64_t)k * ldx + i];
-                if (SGD) v = fmaf(-lr, Grad<GT>::one(g + (int64_t)k * ldg + i), v);
-                x[(int64_t)k * ldx + i] = fmaf(lambda, c - v, v);
-            }
-            if (center_out) center_out[i] = c;
+        for (int k = 0; k < KT; ++k)
+            if (k < K) v[k] = ld_f32<NT>(xi + (int64_t)k * ldx);
+        if (SGD) {
+            const GT *gi = g + i;
+#pragma unroll
+            for (int k = 0; k < KT; ++k)
+                if (k < K) v[k] = fmaf(-lr, Grad<GT>::template ld<NT>(gi + (int64_t)k * ldg), v[k]);
         }
     }
 
-    const int nvec = (int)((b_al - a_al) / 4);
-    float *xb = x + a_al;
-    const GT *gb = g + a_al;
-    for (int j0 = tid; j0 < nvec; j0 += U * GRAWA_BLOCK) {
-        float4 v[U][KT];
+    const int info = cell_layer ? cell_layer[blockIdx.x] : 0;
+    float c = 0.f;
+    if (info >= 0) {
+        const float *b = beta + info;
 #pragma unroll
-        for (int u = 0; u < U; ++u) {
-            const int j = j0 + u * GRAWA_BLOCK;
-            if (j < nvec) {
+        for (int k = 0; k < KT; ++k)
+            if (k < K) c = fmaf(b[(int64_t)k * beta_stride], ok ? v[k] : 0.f, c);
+    } else if (ok) {
+        const float *b = beta + layer_of(off, ~info, L, i);
 #pragma unroll
-                for (int k = 0; k < KT; ++k)
-                    if (k < K) v[u][k] = *reinterpret_cast<const float4 *>(xb + (int64_t)k * ldx + 4 * (int64_t)j);
-                if (SGD) {
+        for (int k = 0; k < KT; ++k)
+            if (k < K) c = fmaf(b[(int64_t)k * beta_stride], v[k], c);
+    }
+
+    if (ok) {
 #pragma unroll
-                    for (int k = 0; k < KT; ++k)
-                        if (k < K) v[u][k] = axpy4(lr, Grad<GT>::quad(gb + (int64_t)k * ldg + 4 * (int64_t)j), v[u][k]);
-                }
-            }
-        }
-#pragma unroll
-        for (int u = 0; u < U; ++u) {
-            const int j = j0 + u * GRAWA_BLOCK;
-            if (j < nvec) {
-                float4 c = make_float4(0.f, 0.f, 0.f, 0.f);
-#pragma unroll
-                for (int k = 0; k < KT; ++k)
-                    if (k < K) {
-                        c.x = fmaf(bk[k], v[u][k].x, c.x);
-                        c.y = fmaf(bk[k], v[u][k].y, c.y);
-                        c.z = fmaf(bk[k], v[u][k].z, c.z);
-                        c.w = fmaf(bk[k], v[u][k].w, c.w);
-                    }
-#pragma unroll
-                for (int k = 0; k < KT; ++k)
-                    if (k < K) {
-                        float4 o;
-                        o.x = fmaf(lambda, c.x - v[u][k].x, v[u][k].x);
-                        o.y = fmaf(lambda, c.y - v[u][k].y, v[u][k].y);
-                        o.z = fmaf(lambda, c.z - v[u][k].z, v[u][k].z);
-                        o.w = fmaf(lambda, c.w - v[u][k].w, v[u][k].w);
-                        *reinterpret_cast<float4 *>(xb + (int64_t)k * ldx + 4 * (int64_t)j) = o;
-                    }
-                if (center_out) *reinterpret_cast<float4 *>(center_out + a_al + 4 * (int64_t)j) = c;
-            }
-        }
+        for (int k = 0; k < KT; ++k)
+            if (k < K) st_f32<NT>(xi + (int64_t)k * ldx, fmaf(lambda, c - v[k], v[k]));
+        if (center_out) st_f32<NT>(center_out + i, c);
     }
 }
 
@@ -380,65 +367,50 @@ __global__ __launch_bounds__(GRAWA_BLOCK) void k_center_pull(
 // first just fetched, normally from cache).  Used only when K exceeds the register-resident
 // variants above.
 template <bool SGD, typename GT>
-__global__ __launch_bounds__(GRAWA_BLOCK) void k_center_pull_any(
+__global__ __launch_bounds__(GRAWA_CELL) void k_center_pull_any(
     float *__restrict__ x, int64_t ldx, const GT *__restrict__ g, int64_t ldg, float lr,
-    const float *__restrict__ beta, int64_t beta_stride, int per_layer,
-    const GrawaTile *__restrict__ tiles, int K, float lambda, float *__restrict__ center_out)
+    const float *__restrict__ beta, int64_t beta_stride, const int32_t *__restrict__ cell_layer,
+    const int64_t *__restrict__ off, int L, int K, int64_t P, float lambda,
+    float *__restrict__ center_out)
 {
-    const GrawaTile t = tiles[blockIdx.x];
-    const int bcol = per_layer ? t.layer : 0;
-    for (int64_t i = t.start + threadIdx.x; i < t.start + t.len; i += GRAWA_BLOCK) {
-        float c = 0.f;
-        for (int k = 0; k < K; ++k) {
-            float v = x[(int64_t)k * ldx + i];
-            if (SGD) v = fmaf(-lr, Grad<GT>::one(g + (int64_t)k * ldg + i), v);
-            c = fmaf(beta[(int64_t)k * beta_stride + bcol], v, c);
-        }
-        for (int k = 0; k < K; ++k) {
-            float v = x[(int64_t)k * ldx + i];
-            if (SGD) v = fmaf(-lr, Grad<GT>::one(g + (int64_t)k * ldg + i), v);
-            x[(int64_t)k * ldx + i] = fmaf(lambda, c - v, v);
-        }
-        if (center_out) center_out[i] = c;
+    const int64_t i = (int64_t)blockIdx.x * GRAWA_CELL + threadIdx.x;
+    if (i >= P) return;
+    int layer = 0;
+    if (cell_layer) {
+        const int info = cell_layer[blockIdx.x];
+        layer = info >= 0 ? info : layer_of(off, ~info, L, i);
     }
+    const float *b = beta + layer;
+    float c = 0.f;
+    for (int k = 0; k < K; ++k) {
+        float v = x[(int64_t)k * ldx + i];
+        if (SGD) v = fmaf(-lr, Grad<GT>::one(g + (int64_t)k * ldg + i), v);
+        c = fmaf(b[(int64_t)k * beta_stride], v, c);
+    }
+    for (int k = 0; k < K; ++k) {
+        float v = x[(int64_t)k * ldx + i];
+        if (SGD) v = fmaf(-lr, Grad<GT>::one(g + (int64_t)k * ldg + i), v);
+        x[(int64_t)k * ldx + i] = fmaf(lambda, c - v, v);
+    }
+    if (center_out) center_out[i] = c;
 }
 
 // ---------------------------------------------------------------------------------
 // local SGD step
 // ---------------------------------------------------------------------------------
 
-#define GRAWA_SGD_U 4 // float4 columns per lane
-
-// grid (ceil(P / (256*4*U)), K), block 256.  x[k][i] -= lr * g[k][i].
-template <typename GT>
-__global__ __launch_bounds__(GRAWA_BLOCK) void k_local_sgd(float *__restrict__ x, int64_t ldx,
-                                                           const GT *__restrict__ g, int64_t ldg,
-                                                           int64_t P, float lr)
+// grid (ceil(P/256), K), block 256.  x[k][i] -= lr * g[k][i], one column per lane.
+template <typename GT, bool NT>
+__global__ __launch_bounds__(GRAWA_CELL) void k_local_sgd(float *__restrict__ x, int64_t ldx,
+                                                          const GT *__restrict__ g, int64_t ldg,
+                                                          int64_t P, float lr)
 {
-    const int k = blockIdx.y;
-    float *xr = x + (int64_t)k * ldx;
-    const GT *gr = g + (int64_t)k * ldg;
-    const int64_t nvec = P / 4;
-    const int64_t j0 = (int64_t)blockIdx.x * (GRAWA_SGD_U * GRAWA_BLOCK) + threadIdx.x;
-    float4 xv[GRAWA_SGD_U], gv[GRAWA_SGD_U];
-#pragma unroll
-    for (int u = 0; u < GRAWA_SGD_U; ++u) {
-        const int64_t j = j0 + u * GRAWA_BLOCK;
-        if (j < nvec) {
-            xv[u] = *reinterpret_cast<const float4 *>(xr + 4 * j);
-            gv[u] = Grad<GT>::quad(gr + 4 * j);
-        }
-    }
-#pragma unroll
-    for (int u = 0; u < GRAWA_SGD_U; ++u) {
-        const int64_t j = j0 + u * GRAWA_BLOCK;
-        if (j < nvec) *reinterpret_cast<float4 *>(xr + 4 * j) = axpy4(lr, gv[u], xv[u]);
-    }
-    // the last P % 4 elements of the row
-    if (blockIdx.x == 0 && threadIdx.x < (int)(P - nvec * 4)) {
-        const int64_t i = nvec * 4 + threadIdx.x;
-        xr[i] = fmaf(-lr, Grad<GT>::one(gr + i), xr[i]);
-    }
+    const int64_t i = (int64_t)blockIdx.x * GRAWA_CELL + threadIdx.x;
+    if (i >= P) return;
+    float *xp = x + (int64_t)blockIdx.y * ldx + i;
+    const float xv = ld_f32<NT>(xp);
+    const float gv = Grad<GT>::template ld<NT>(g + (int64_t)blockIdx.y * ldg + i);
+    st_f32<NT>(xp, fmaf(-lr, gv, xv));
 }
 
 // ---------------------------------------------------------------------------------
@@ -490,29 +462,37 @@ hipError_t grawa_launch_finalize_model(const grawa_plan *p, grawa_norm_mode_t mo
     return hipGetLastError();
 }
 
-template <int KT, int U, bool SGD, typename GT>
+template <int KT, bool SGD, typename GT, bool NT>
 static void launch_cp(const grawa_plan *p, float *x, int64_t ldx, const void *g, int64_t ldg, float lr,
                       const float *beta, int per_layer, float lambda, float *center_out, hipStream_t s)
 {
-    k_center_pull<KT, U, SGD, GT><<<dim3((unsigned)p->n_tiles), dim3(GRAWA_BLOCK), 0, s>>>(
-        x, ldx, (const GT *)g, ldg, lr, beta, per_layer ? (int64_t)p->L : 1, per_layer, p->d_tiles,
-        p->K, lambda, center_out);
+    k_center_pull<KT, SGD, GT, NT><<<dim3((unsigned)p->n_cells), dim3(GRAWA_CELL), 0, s>>>(
+        x, ldx, (const GT *)g, ldg, lr, beta, per_layer ? (int64_t)p->L : 1,
+        per_layer ? p->d_cell_layer : nullptr, p->d_off, p->L, p->K, p->P, lambda, center_out);
 }
 
-template <bool SGD, typename GT>
+template <bool SGD, typename GT, bool NT>
 static void dispatch_cp(const grawa_plan *p, float *x, int64_t ldx, const void *g, int64_t ldg, float lr,
                         const float *beta, int per_layer, float lambda, float *center_out, hipStream_t s)
 {
     const int K = p->K;
-    if (K <= 2) launch_cp<2, 8, SGD, GT>(p, x, ldx, g, ldg, lr, beta, per_layer, lambda, center_out, s);
-    else if (K <= 4) launch_cp<4, 4, SGD, GT>(p, x, ldx, g, ldg, lr, beta, per_layer, lambda, center_out, s);
-    else if (K <= 8) launch_cp<8, 2, SGD, GT>(p, x, ldx, g, ldg, lr, beta, per_layer, lambda, center_out, s);
-    else if (K <= 16) launch_cp<16, 1, SGD, GT>(p, x, ldx, g, ldg, lr, beta, per_layer, lambda, center_out, s);
-    else if (K <= 32) launch_cp<32, 1, SGD, GT>(p, x, ldx, g, ldg, lr, beta, per_layer, lambda, center_out, s);
+    if (K <= 2) launch_cp<2, SGD, GT, NT>(p, x, ldx, g, ldg, lr, beta, per_layer, lambda, center_out, s);
+    else if (K <= 4) launch_cp<4, SGD, GT, NT>(p, x, ldx, g, ldg, lr, beta, per_layer, lambda, center_out, s);
+    else if (K <= 8) launch_cp<8, SGD, GT, NT>(p, x, ldx, g, ldg, lr, beta, per_layer, lambda, center_out, s);
+    else if (K <= 16) launch_cp<16, SGD, GT, NT>(p, x, ldx, g, ldg, lr, beta, per_layer, lambda, center_out, s);
+    else if (K <= 32) launch_cp<32, SGD, GT, NT>(p, x, ldx, g, ldg, lr, beta, per_layer, lambda, center_out, s);
+    else if (K <= 64) launch_cp<64, SGD, GT, NT>(p, x, ldx, g, ldg, lr, beta, per_layer, lambda, center_out, s);
     else
-        k_center_pull_any<SGD, GT><<<dim3((unsigned)p->n_tiles), dim3(GRAWA_BLOCK), 0, s>>>(
-            x, ldx, (const GT *)g, ldg, lr, beta, per_layer ? (int64_t)p->L : 1, per_layer, p->d_tiles, K,
-            lambda, center_out);
+        k_center_pull_any<SGD, GT><<<dim3((unsigned)p->n_cells), dim3(GRAWA_CELL), 0, s>>>(
+            x, ldx, (const GT *)g, ldg, lr, beta, per_layer ? (int64_t)p->L : 1,
+            per_layer ? p->d_cell_layer : nullptr, p->d_off, p->L, K, p->P, lambda, center_out);
+}
+
+// Streaming accesses are used only when no cache line is shared between two rows or written
+// in two parts: base pointers and row pitches are multiples of 128 bytes.
+static bool rows_line_aligned(const void *base, int64_t ld, int elem_bytes)
+{
+    return (reinterpret_cast<uintptr_t>(base) % 128u) == 0 && ((ld * elem_bytes) % 128) == 0;
 }
 
 hipError_t grawa_launch_center_pull(const grawa_plan *p, float *x, int64_t ldx, const float *beta,
@@ -520,26 +500,34 @@ hipError_t grawa_launch_center_pull(const grawa_plan *p, float *x, int64_t ldx, 
                                     grawa_dtype_t dt, float lr, int fuse_sgd, float *center_out,
                                     hipStream_t s)
 {
-    if (!fuse_sgd)
-        dispatch_cp<false, float>(p, x, ldx, nullptr, 0, 0.f, beta, per_layer, lambda, center_out, s);
-    else if (dt == GRAWA_BF16)
-        dispatch_cp<true, uint16_t>(p, x, ldx, g_sgd, ldg_sgd, lr, beta, per_layer, lambda, center_out, s);
-    else
-        dispatch_cp<true, float>(p, x, ldx, g_sgd, ldg_sgd, lr, beta, per_layer, lambda, center_out, s);
+    bool nt = rows_line_aligned(x, ldx, 4) && (!center_out || rows_line_aligned(center_out, 0, 4));
+    if (fuse_sgd) nt = nt && rows_line_aligned(g_sgd, ldg_sgd, dt == GRAWA_BF16 ? 2 : 4);
+    if (!fuse_sgd) {
+        if (nt) dispatch_cp<false, float, true>(p, x, ldx, nullptr, 0, 0.f, beta, per_layer, lambda, center_out, s);
+        else dispatch_cp<false, float, false>(p, x, ldx, nullptr, 0, 0.f, beta, per_layer, lambda, center_out, s);
+    } else if (dt == GRAWA_BF16) {
+        if (nt) dispatch_cp<true, uint16_t, true>(p, x, ldx, g_sgd, ldg_sgd, lr, beta, per_layer, lambda, center_out, s);
+        else dispatch_cp<true, uint16_t, false>(p, x, ldx, g_sgd, ldg_sgd, lr, beta, per_layer, lambda, center_out, s);
+    } else {
+        if (nt) dispatch_cp<true, float, true>(p, x, ldx, g_sgd, ldg_sgd, lr, beta, per_layer, lambda, center_out, s);
+        else dispatch_cp<true, float, false>(p, x, ldx, g_sgd, ldg_sgd, lr, beta, per_layer, lambda, center_out, s);
+    }
     return hipGetLastError();
 }
 
 hipError_t grawa_launch_local_sgd(float *x, int64_t ldx, const void *g, int64_t ldg, grawa_dtype_t dt,
                                   int K, int64_t P, float lr, hipStream_t s)
 {
-    const int64_t nvec = P / 4;
-    int64_t gx = (nvec + GRAWA_SGD_U * GRAWA_BLOCK - 1) / (GRAWA_SGD_U * GRAWA_BLOCK);
-    if (gx < 1) gx = 1;
-    const dim3 grid((unsigned)gx, (unsigned)K), block(GRAWA_BLOCK);
-    if (dt == GRAWA_BF16)
-        k_local_sgd<uint16_t><<<grid, block, 0, s>>>(x, ldx, (const uint16_t *)g, ldg, P, lr);
-    else
-        k_local_sgd<float><<<grid, block, 0, s>>>(x, ldx, (const float *)g, ldg, P, lr);
+    const int64_t gx = (P + GRAWA_CELL - 1) / GRAWA_CELL;
+    const dim3 grid((unsigned)gx, (unsigned)K), block(GRAWA_CELL);
+    const bool nt = rows_line_aligned(x, ldx, 4) && rows_line_aligned(g, ldg, dt == GRAWA_BF16 ? 2 : 4);
+    if (dt == GRAWA_BF16) {
+        if (nt) k_local_sgd<uint16_t, true><<<grid, block, 0, s>>>(x, ldx, (const uint16_t *)g, ldg, P, lr);
+        else k_local_sgd<uint16_t, false><<<grid, block, 0, s>>>(x, ldx, (const uint16_t *)g, ldg, P, lr);
+    } else {
+        if (nt) k_local_sgd<float, true><<<grid, block, 0, s>>>(x, ldx, (const float *)g, ldg, P, lr);
+        else k_local_sgd<float, false><<<grid, block, 0, s>>>(x, ldx, (const float *)g, ldg, P, lr);
+    }
     return hipGetLastError();
 }
 

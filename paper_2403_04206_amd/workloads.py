@@ -169,6 +169,9 @@ N_CONFIGS = 5
 # input arrays
 # ----------------------------------------------------------------------------
 
+ROW_ALIGN = 256   # elements: 1 KiB pitch granularity for fp32 rows, 512 B for bf16 rows
+
+
 def round_up(n, m):
     return (n + m - 1) // m * m
 
@@ -184,14 +187,16 @@ def grad_scales(w: Workload) -> np.ndarray:
 
 def make_inputs(w: Workload, device="cpu", ld_pad: int = 0, param_std: float = 0.05):
     """Draw x ~ N(0, param_std^2) (float32 [K, ld]) and g[k, layer l] ~ N(0, s[k,l]^2)
-    (float32, or bfloat16 rounded to nearest even from float32), ld = P rounded up to 8
-    elements plus ld_pad.  Returns torch tensors on `device`; the padding columns hold
-    a large sentinel so that a kernel that touches them is noticed."""
+    (float32, or bfloat16 rounded to nearest even from float32).  The row pitch ld is P
+    rounded up to ROW_ALIGN elements (so that every row starts on a cache-line boundary, the
+    layout the library is fastest on) plus ld_pad (to break that alignment on purpose).
+    Returns torch tensors on `device`; the padding columns hold a large sentinel so that a
+    kernel that touches them is noticed."""
     dev = torch.device(device)
     gen = torch.Generator(device=dev)
     gen.manual_seed(int(w.seed[0]) * 1_000_003 + int(w.seed[1]) * 7919 + 12345)
     P, K = w.P, w.K
-    ld = round_up(P, 8) + ld_pad
+    ld = round_up(P, ROW_ALIGN) + ld_pad
     s = torch.from_numpy(grad_scales(w)).to(torch.float32).to(dev)
     sizes = torch.from_numpy(np.diff(w.offsets)).to(dev)
     x = torch.empty((K, ld), dtype=torch.float32, device=dev)
