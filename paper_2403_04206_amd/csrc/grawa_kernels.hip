@@ -90,13 +90,31 @@ __device__ __forceinline__ double block_min(double v, double *sm)
 typedef float v4f __attribute__((ext_vector_type(4)));
 typedef unsigned int v4u __attribute__((ext_vector_type(4)));
 
-// Scalar (one element per lane) loads and stores, streaming (non-temporal) or plain.
-template <bool NT> __device__ __forceinline__ float ld_f32(const float *p)
+// Global-memory accessors for the one-element-per-lane kernels.  An address is a wave-uniform
+// 64-bit base plus a 32-bit lane byte offset; the base is pinned in a scalar register pair so
+// that the access is issued in that form instead of with a 64-bit address computed per lane.
+// NT = streaming (non-temporal) access.
+#define GRAWA_GLOBAL __attribute__((address_space(1)))
+
+__device__ __forceinline__ uint64_t uniform_base(const void *p)
 {
+    uint64_t a = reinterpret_cast<uint64_t>(p);
+    asm volatile("" : "+s"(a));
+    return a;
+}
+// A float read through the scalar unit from memory this kernel never writes.
+__device__ __forceinline__ float ld_uniform_f32(uint64_t base, int64_t index)
+{
+    return ((const __attribute__((address_space(4))) float *)base)[index];
+}
+template <bool NT, typename T> __device__ __forceinline__ T ld_lane(uint64_t base, unsigned byte_off)
+{
+    const GRAWA_GLOBAL T *p = (const GRAWA_GLOBAL T *)(base + byte_off);
     return NT ? __builtin_nontemporal_load(p) : *p;
 }
-template <bool NT> __device__ __forceinline__ void st_f32(float *p, float v)
+template <bool NT, typename T> __device__ __forceinline__ void st_lane(uint64_t base, unsigned byte_off, T v)
 {
+    GRAWA_GLOBAL T *p = (GRAWA_GLOBAL T *)(base + byte_off);
     if (NT) __builtin_nontemporal_store(v, p);
     else *p = v;
 }
@@ -107,7 +125,10 @@ template <typename GT> struct Grad;
 template <> struct Grad<float> {
     static constexpr int VEC16 = 4;
     static __device__ __forceinline__ float one(const float *p) { return *p; }
-    template <bool NT> static __device__ __forceinline__ float ld(const float *p) { return ld_f32<NT>(p); }
+    template <bool NT> static __device__ __forceinline__ float lane(uint64_t base, unsigned off)
+    {
+        return ld_lane<NT, float>(base, off);
+    }
     // acc + sum of squares of the 4 floats at p (16-byte aligned), streaming load
     static __device__ __forceinline__ float sumsq16(const float *p, float acc)
     {
@@ -123,9 +144,9 @@ template <> struct Grad<float> {
 template <> struct Grad<uint16_t> { // bfloat16 bit patterns
     static constexpr int VEC16 = 8;
     static __device__ __forceinline__ float one(const uint16_t *p) { return bf16_one(*p); }
-    template <bool NT> static __device__ __forceinline__ float ld(const uint16_t *p)
+    template <bool NT> static __device__ __forceinline__ float lane(uint64_t base, unsigned off)
     {
-        return bf16_one(NT ? __builtin_nontemporal_load(p) : *p);
+        return bf16_one(ld_lane<NT, uint16_t>(base, off));
     }
     static __device__ __forceinline__ float sumsq16(const uint16_t *p, float acc)
     {
@@ -311,55 +332,62 @@ __device__ __forceinline__ int layer_of(const int64_t *__restrict__ off, int lay
 // x[k][i] for all K workers (K independent loads in flight; with SGD also g[k][i] and applies
 // x - lr g), forms c = sum_k beta_k x_k and writes x_k + lambda (c - x_k) back, so every
 // parameter is read once and written once.  A wave touches one 256-byte piece per row.
-// KT = compile-time bound on K.  NT = streaming loads/stores, chosen by the host only when
-// every row starts on a 128-byte boundary.
+// KT = number of register slots; EXACT says K == KT (no per-row guards, the usual case),
+// otherwise K <= KT.  NT = streaming loads/stores, chosen by the host only when every row
+// starts on a 128-byte boundary.  Row bases are wave-uniform, the lane adds only its index.
 // cell_layer[m] >= 0: the whole block lies in that layer (weights come through scalar
 // loads); < 0: the block contains a layer boundary, ~cell_layer[m] is the layer of its first
 // column and each lane finds its own layer.  Model-level weights pass cell_layer = nullptr.
 // The pull is x + lambda (c - x), one fma, which leaves a single worker exactly unchanged.
-template <int KT, bool SGD, typename GT, bool NT>
+template <int KT, bool EXACT, bool SGD, typename GT, bool NT>
 __global__ __launch_bounds__(GRAWA_CELL) void k_center_pull(
     float *__restrict__ x, int64_t ldx, const GT *__restrict__ g, int64_t ldg, float lr,
     const float *__restrict__ beta, int64_t beta_stride, const int32_t *__restrict__ cell_layer,
     const int64_t *__restrict__ off, int L, int K, int64_t P, float lambda,
     float *__restrict__ center_out)
 {
-    const int64_t i = (int64_t)blockIdx.x * GRAWA_CELL + threadIdx.x;
-    const bool ok = i < P;
-    float *xi = x + i;
+    const int64_t cell0 = (int64_t)blockIdx.x * GRAWA_CELL; // wave-uniform
+    const unsigned t = threadIdx.x;
+    const bool ok = cell0 + t < P;
+    float *xb = x + cell0;
+    const GT *gb = g + cell0;
+    const unsigned xoff = t * 4u, goff = t * (unsigned)sizeof(GT);
+    const int nk = EXACT ? KT : K;
 
     float v[KT];
+#pragma unroll
+    for (int k = 0; k < KT; ++k) v[k] = 0.f;
     if (ok) {
 #pragma unroll
         for (int k = 0; k < KT; ++k)
-            if (k < K) v[k] = ld_f32<NT>(xi + (int64_t)k * ldx);
+            if (k < nk) v[k] = ld_lane<NT, float>(uniform_base(xb + (int64_t)k * ldx), xoff);
         if (SGD) {
-            const GT *gi = g + i;
 #pragma unroll
             for (int k = 0; k < KT; ++k)
-                if (k < K) v[k] = fmaf(-lr, Grad<GT>::template ld<NT>(gi + (int64_t)k * ldg), v[k]);
+                if (k < nk)
+                    v[k] = fmaf(-lr, Grad<GT>::template lane<NT>(uniform_base(gb + (int64_t)k * ldg), goff), v[k]);
         }
     }
 
     const int info = cell_layer ? cell_layer[blockIdx.x] : 0;
     float c = 0.f;
-    if (info >= 0) {
-        const float *b = beta + info;
+    if (info >= 0) { // one layer for the whole block: weights through scalar loads
+        const uint64_t bb = uniform_base(beta + info);
 #pragma unroll
         for (int k = 0; k < KT; ++k)
-            if (k < K) c = fmaf(b[(int64_t)k * beta_stride], ok ? v[k] : 0.f, c);
-    } else if (ok) {
-        const float *b = beta + layer_of(off, ~info, L, i);
+            if (k < nk) c = fmaf(ld_uniform_f32(bb, (int64_t)k * beta_stride), v[k], c);
+    } else if (ok) { // the block holds a layer boundary: each lane looks up its own layer
+        const float *b = beta + layer_of(off, ~info, L, cell0 + t);
 #pragma unroll
         for (int k = 0; k < KT; ++k)
-            if (k < K) c = fmaf(b[(int64_t)k * beta_stride], v[k], c);
+            if (k < nk) c = fmaf(b[(int64_t)k * beta_stride], v[k], c);
     }
 
     if (ok) {
 #pragma unroll
         for (int k = 0; k < KT; ++k)
-            if (k < K) st_f32<NT>(xi + (int64_t)k * ldx, fmaf(lambda, c - v[k], v[k]));
-        if (center_out) st_f32<NT>(center_out + i, c);
+            if (k < nk) st_lane<NT, float>(uniform_base(xb + (int64_t)k * ldx), xoff, fmaf(lambda, c - v[k], v[k]));
+        if (center_out) st_lane<NT, float>(uniform_base(center_out + cell0), xoff, c);
     }
 }
 
@@ -405,12 +433,14 @@ __global__ __launch_bounds__(GRAWA_CELL) void k_local_sgd(float *__restrict__ x,
                                                           const GT *__restrict__ g, int64_t ldg,
                                                           int64_t P, float lr)
 {
-    const int64_t i = (int64_t)blockIdx.x * GRAWA_CELL + threadIdx.x;
-    if (i >= P) return;
-    float *xp = x + (int64_t)blockIdx.y * ldx + i;
-    const float xv = ld_f32<NT>(xp);
-    const float gv = Grad<GT>::template ld<NT>(g + (int64_t)blockIdx.y * ldg + i);
-    st_f32<NT>(xp, fmaf(-lr, gv, xv));
+    const int64_t cell0 = (int64_t)blockIdx.x * GRAWA_CELL;
+    const unsigned t = threadIdx.x;
+    if (cell0 + t >= P) return;
+    const uint64_t xr = uniform_base(x + (int64_t)blockIdx.y * ldx + cell0);
+    const uint64_t gr = uniform_base(g + (int64_t)blockIdx.y * ldg + cell0);
+    const float xv = ld_lane<NT, float>(xr, t * 4u);
+    const float gv = Grad<GT>::template lane<NT>(gr, t * (unsigned)sizeof(GT));
+    st_lane<NT, float>(xr, t * 4u, fmaf(-lr, gv, xv));
 }
 
 // ---------------------------------------------------------------------------------
@@ -462,30 +492,40 @@ hipError_t grawa_launch_finalize_model(const grawa_plan *p, grawa_norm_mode_t mo
     return hipGetLastError();
 }
 
-template <int KT, bool SGD, typename GT, bool NT>
+template <int KT, bool EXACT, bool SGD, typename GT, bool NT>
 static void launch_cp(const grawa_plan *p, float *x, int64_t ldx, const void *g, int64_t ldg, float lr,
                       const float *beta, int per_layer, float lambda, float *center_out, hipStream_t s)
 {
-    k_center_pull<KT, SGD, GT, NT><<<dim3((unsigned)p->n_cells), dim3(GRAWA_CELL), 0, s>>>(
+    k_center_pull<KT, EXACT, SGD, GT, NT><<<dim3((unsigned)p->n_cells), dim3(GRAWA_CELL), 0, s>>>(
         x, ldx, (const GT *)g, ldg, lr, beta, per_layer ? (int64_t)p->L : 1,
         per_layer ? p->d_cell_layer : nullptr, p->d_off, p->L, p->K, p->P, lambda, center_out);
 }
 
+// One kernel per worker count up to 32 (fully unrolled, no guards); 33..64 workers share a
+// guarded 64-slot kernel; beyond that the two-sweep kernel.
 template <bool SGD, typename GT, bool NT>
 static void dispatch_cp(const grawa_plan *p, float *x, int64_t ldx, const void *g, int64_t ldg, float lr,
                         const float *beta, int per_layer, float lambda, float *center_out, hipStream_t s)
 {
+#define GRAWA_CP_CASE(N) \
+    case N: launch_cp<N, true, SGD, GT, NT>(p, x, ldx, g, ldg, lr, beta, per_layer, lambda, center_out, s); break;
     const int K = p->K;
-    if (K <= 2) launch_cp<2, SGD, GT, NT>(p, x, ldx, g, ldg, lr, beta, per_layer, lambda, center_out, s);
-    else if (K <= 4) launch_cp<4, SGD, GT, NT>(p, x, ldx, g, ldg, lr, beta, per_layer, lambda, center_out, s);
-    else if (K <= 8) launch_cp<8, SGD, GT, NT>(p, x, ldx, g, ldg, lr, beta, per_layer, lambda, center_out, s);
-    else if (K <= 16) launch_cp<16, SGD, GT, NT>(p, x, ldx, g, ldg, lr, beta, per_layer, lambda, center_out, s);
-    else if (K <= 32) launch_cp<32, SGD, GT, NT>(p, x, ldx, g, ldg, lr, beta, per_layer, lambda, center_out, s);
-    else if (K <= 64) launch_cp<64, SGD, GT, NT>(p, x, ldx, g, ldg, lr, beta, per_layer, lambda, center_out, s);
-    else
-        k_center_pull_any<SGD, GT><<<dim3((unsigned)p->n_cells), dim3(GRAWA_CELL), 0, s>>>(
-            x, ldx, (const GT *)g, ldg, lr, beta, per_layer ? (int64_t)p->L : 1,
-            per_layer ? p->d_cell_layer : nullptr, p->d_off, p->L, K, p->P, lambda, center_out);
+    switch (K) {
+        GRAWA_CP_CASE(1) GRAWA_CP_CASE(2) GRAWA_CP_CASE(3) GRAWA_CP_CASE(4) GRAWA_CP_CASE(5) GRAWA_CP_CASE(6)
+        GRAWA_CP_CASE(7) GRAWA_CP_CASE(8) GRAWA_CP_CASE(9) GRAWA_CP_CASE(10) GRAWA_CP_CASE(11) GRAWA_CP_CASE(12)
+        GRAWA_CP_CASE(13) GRAWA_CP_CASE(14) GRAWA_CP_CASE(15) GRAWA_CP_CASE(16) GRAWA_CP_CASE(17) GRAWA_CP_CASE(18)
+        GRAWA_CP_CASE(19) GRAWA_CP_CASE(20) GRAWA_CP_CASE(21) GRAWA_CP_CASE(22) GRAWA_CP_CASE(23) GRAWA_CP_CASE(24)
+        GRAWA_CP_CASE(25) GRAWA_CP_CASE(26) GRAWA_CP_CASE(27) GRAWA_CP_CASE(28) GRAWA_CP_CASE(29) GRAWA_CP_CASE(30)
+        GRAWA_CP_CASE(31) GRAWA_CP_CASE(32)
+    default:
+        if (K <= 64)
+            launch_cp<64, false, SGD, GT, NT>(p, x, ldx, g, ldg, lr, beta, per_layer, lambda, center_out, s);
+        else
+            k_center_pull_any<SGD, GT><<<dim3((unsigned)p->n_cells), dim3(GRAWA_CELL), 0, s>>>(
+                x, ldx, (const GT *)g, ldg, lr, beta, per_layer ? (int64_t)p->L : 1,
+                per_layer ? p->d_cell_layer : nullptr, p->d_off, p->L, K, p->P, lambda, center_out);
+    }
+#undef GRAWA_CP_CASE
 }
 
 // Streaming accesses are used only when no cache line is shared between two rows or written
