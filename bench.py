@@ -156,6 +156,26 @@ def cpu_baseline(torch, W, w, variant, target_seconds):
     }
 
 
+def measured_traffic(workload, variant):
+    """HBM bytes per launch of the center+pull kernel from the committed rocprofv3 counter runs
+    (profiles/traffic.json), or None when there is no entry for this workload or the library
+    sources have changed since the counters were taken."""
+    from paper_2403_04206_amd import profile_summary
+    path = os.path.join(ROOT, "profiles", "traffic.json")
+    try:
+        with open(path) as f:
+            tj = json.load(f)
+    except (OSError, ValueError):
+        return None
+    if tj.get("source_hash") != profile_summary.kernel_source_hash():
+        return None
+    entry = tj.get("workloads", {}).get(workload)
+    if not entry or entry.get("variant") != variant:
+        return None
+    k = entry.get("kernels", {}).get("k_center_pull")
+    return k["total_bytes"] if k else None
+
+
 def main():
     a = parse()
     if a.gpus != 1:
@@ -177,7 +197,8 @@ def main():
 
     roofline = {
         "bound": "hbm", "kernel": "k_center_pull", "achieved": stats["pull_kernel_GBps"], "peak": HBM_PEAK_GBPS,
-        "unit": "GB/s", "frac": (stats["pull_kernel_GBps"] or 0.0) / HBM_PEAK_GBPS, "traffic": None,
+        "unit": "GB/s", "frac": (stats["pull_kernel_GBps"] or 0.0) / HBM_PEAK_GBPS,
+        "traffic": measured_traffic(w.name, stats["variant"]),
         "bytes_per_launch": stats["pull_kernel_bytes"], "avg_launch_ms": stats["pull_kernel_ms"],
         "norm_kernel": {"achieved": stats["norm_kernel_GBps"], "avg_launch_ms": stats["norm_kernel_ms"],
                         "frac": (stats["norm_kernel_GBps"] or 0.0) / HBM_PEAK_GBPS},

@@ -394,7 +394,7 @@ grawa_status_t grawa_stream_copy(void *dst, const void *src, int64_t nbytes, voi
 {
     if (!dst || !src || nbytes < 0) return GRAWA_ERR_INVALID_ARG;
     if (!aligned16(dst) || !aligned16(src) || (nbytes % 16) != 0) return GRAWA_ERR_ALIGNMENT;
-    if (nbytes / 16 > ((int64_t)1 << 34)) return GRAWA_ERR_UNSUPPORTED;
+    if (nbytes / 16 >= ((int64_t)1 << 32)) return GRAWA_ERR_UNSUPPORTED; /* grid.x * 64 < 2^32 */
     GRAWA_TRY_HIP(grawa_launch_stream_copy(dst, src, nbytes, static_cast<hipStream_t>(stream)));
     return GRAWA_OK;
 }

@@ -1,0 +1,166 @@
+"""Turn rocprofv3 CSV output of bench.py runs into the short text summaries kept under
+profiles/ and into profiles/traffic.json (HBM bytes per launch of the update kernels).
+
+Expected input, one directory per run (any parent folder):
+    <dir>/prof_cfg<N>_stats   from  rocprofv3 --kernel-trace --stats -d <that dir> --output-format csv
+                                    -- python3 bench.py --config <N> --no-sweep --no-cpu-baseline
+    <dir>/prof_cfg<N>_fetch   same command with  --pmc FETCH_SIZE   instead of --kernel-trace --stats
+    <dir>/prof_cfg<N>_write   same command with  --pmc WRITE_SIZE
+
+FETCH_SIZE / WRITE_SIZE are reported in KiB per dispatch.  Each is scaled by what the same
+counter reads, in the same run, for the library's plain copy kernel (bench.py launches it over
+2 GiB: 2 GiB read, 2 GiB written), because the raw counters do not weigh every request size
+correctly (streaming loads are counted at half their size on this part).
+
+usage: python -m paper_2403_04206_amd.profile_summary <dir with prof_cfg*_*> [configs...]
+"""
+from __future__ import annotations
+
+import collections
+import csv
+import glob
+import hashlib
+import json
+import os
+import sys
+
+PKG = os.path.dirname(os.path.abspath(__file__))
+ROOT = os.path.dirname(PKG)
+COPY_BYTES = 1 << 31
+
+
+def kernel_source_hash() -> str:
+    h = hashlib.sha256()
+    for name in ("grawa_kernels.hip", "grawa_api.cpp", "grawa_internal.h"):
+        with open(os.path.join(PKG, "csrc", name), "rb") as f:
+            h.update(f.read())
+    return h.hexdigest()[:16]
+
+
+def short(name: str) -> str:
+    name = name.strip('"')
+    if name.startswith("void "):
+        name = name[5:]
+    return name.split("(")[0]
+
+
+def read_counters(run_dir: str, counter: str):
+    files = glob.glob(os.path.join(run_dir, "*", "*counter_collection.csv"))
+    if not files:
+        raise FileNotFoundError("no counter_collection.csv under " + run_dir)
+    agg = collections.defaultdict(list)
+    for r in csv.DictReader(open(files[0])):
+        if r["Counter_Name"] == counter:
+            agg[short(r["Kernel_Name"])].append(float(r["Counter_Value"]))
+    return {k: (sum(v) / len(v), len(v)) for k, v in agg.items()}
+
+
+def read_stats(run_dir: str):
+    files = glob.glob(os.path.join(run_dir, "*", "*kernel_stats.csv"))
+    if not files:
+        raise FileNotFoundError("no kernel_stats.csv under " + run_dir)
+    return [(short(r["Name"]), int(r["Calls"]), float(r["AverageNs"]), float(r["MinNs"]), float(r["MaxNs"]),
+             float(r["Percentage"])) for r in csv.DictReader(open(files[0]))]
+
+
+def bench_line(run_dir: str):
+    with open(os.path.join(run_dir, "run.log")) as f:
+        for line in f:
+            if line.startswith("{") and '"metric"' in line:
+                return json.loads(line)
+    return None
+
+
+def summarize(base: str, cfg: int, out_dir: str):
+    stats_dir = os.path.join(base, "prof_cfg%d_stats" % cfg)
+    stats = read_stats(stats_dir)
+    bl = bench_line(stats_dir)
+    fetch = read_counters(os.path.join(base, "prof_cfg%d_fetch" % cfg), "FETCH_SIZE")
+    write = read_counters(os.path.join(base, "prof_cfg%d_write" % cfg), "WRITE_SIZE")
+    copy_f = fetch["k_stream_copy"][0] * 1024.0
+    copy_w = write["k_stream_copy"][0] * 1024.0
+    f_scale, w_scale = COPY_BYTES / copy_f, COPY_BYTES / copy_w
+    w = bl["config"]
+    K, P = w["K"], w["P"]
+    gb = 2 if w["grad_dtype"] == "bf16" else 4
+    fused = w["variant"].endswith("+sgd")
+    algo = {"k_sumsq": K * P * gb, "k_center_pull": K * P * (8 + (gb if fused else 0))}
+
+    lines = []
+    lines.append("# rocprofv3 summary: GRAWA update kernels, %s (%s)" % (w["workload"], w["variant"]))
+    lines.append("")
+    lines.append("K=%d workers, L=%d layers, P=%d parameters, gradients %s, library source hash %s." %
+                 (K, w["L"], P, w["grad_dtype"], kernel_source_hash()))
+    lines.append("")
+    lines.append("Commands (run from /tmp with TMPDIR=/tmp, repository root = $R):")
+    lines.append("")
+    for args in ("--kernel-trace --stats", "--pmc FETCH_SIZE", "--pmc WRITE_SIZE"):
+        lines.append("    rocprofv3 %s -d <out> --output-format csv -- python3 $R/bench.py --config %d --no-sweep "
+                     "--no-cpu-baseline" % (args, cfg))
+    lines.append("")
+    lines.append("bench.py line of the --kernel-trace run: value %.0f GB/s (%.1f%% of 8 TB/s), %.4f ms/update, "
+                 "%.0f updates/s; center+pull kernel from HIP events %.4f ms/launch." %
+                 (bl["value"], 100 * bl["frac_of_hbm_peak"], bl["ms_per_step"], bl["updates_per_s"],
+                  bl["roofline"]["avg_launch_ms"]))
+    lines.append("")
+    lines.append("## --kernel-trace --stats (library kernels only)")
+    lines.append("")
+    lines.append("| kernel | calls | avg us | min us | max us | algorithmic bytes/launch | GB/s at avg | % of 8 TB/s |")
+    lines.append("|---|---|---|---|---|---|---|---|")
+    traffic = {}
+    for name, calls, avg, mn, mx, _pct in stats:
+        base_name = name.split("<")[0]
+        if not base_name.startswith(("k_", "grawa")):
+            continue
+        ab = algo.get(base_name)
+        if base_name == "k_stream_copy":
+            ab = 2 * COPY_BYTES
+        gbps = "%.0f" % (ab / avg) if ab else "-"
+        frac = "%.1f" % (100 * ab / avg / 8000.0) if ab else "-"
+        lines.append("| %s | %d | %.1f | %.1f | %.1f | %s | %s | %s |" %
+                     (name, calls, avg / 1e3, mn / 1e3, mx / 1e3, ab if ab else "-", gbps, frac))
+    lines.append("")
+    lines.append("## HBM traffic per launch (--pmc FETCH_SIZE, --pmc WRITE_SIZE; KiB per dispatch, averaged)")
+    lines.append("")
+    lines.append("Calibration on the plain copy kernel of the same run (2 GiB read + 2 GiB written): FETCH_SIZE reads "
+                 "%.0f KiB (scale %.4f), WRITE_SIZE reads %.0f KiB (scale %.4f)." %
+                 (copy_f / 1024, f_scale, copy_w / 1024, w_scale))
+    lines.append("")
+    lines.append("| kernel | FETCH_SIZE KiB | WRITE_SIZE KiB | scaled read bytes | scaled written bytes | scaled total | "
+                 "algorithmic bytes | total / algorithmic |")
+    lines.append("|---|---|---|---|---|---|---|---|")
+    for name in sorted(fetch):
+        base_name = name.split("<")[0]
+        if base_name not in algo:
+            continue
+        fr = fetch[name][0] * 1024 * f_scale
+        wr = write.get(name, (0.0, 0))[0] * 1024 * w_scale
+        tot = fr + wr
+        lines.append("| %s | %.0f | %.0f | %.4g | %.4g | %.4g | %d | %.4f |" %
+                     (name, fetch[name][0], write.get(name, (0.0, 0))[0], fr, wr, tot, algo[base_name],
+                      tot / algo[base_name]))
+        traffic[base_name] = {"kernel": name, "read_bytes": fr, "written_bytes": wr, "total_bytes": tot,
+                              "algorithmic_bytes": algo[base_name]}
+    lines.append("")
+    name = "update_kernels_%s.md" % w["workload"]
+    with open(os.path.join(out_dir, name), "w") as f:
+        f.write("\n".join(lines) + "\n")
+    return w["workload"], {"variant": w["variant"], "fetch_scale": f_scale, "write_scale": w_scale, "kernels": traffic}
+
+
+def main(argv):
+    base = argv[1]
+    cfgs = [int(a) for a in argv[2:]] or [2, 3, 4]
+    out_dir = os.path.join(ROOT, "profiles")
+    os.makedirs(out_dir, exist_ok=True)
+    tj = {"source_hash": kernel_source_hash(), "workloads": {}}
+    for c in cfgs:
+        name, t = summarize(base, c, out_dir)
+        tj["workloads"][name] = t
+        print("wrote summary for", name)
+    with open(os.path.join(out_dir, "traffic.json"), "w") as f:
+        json.dump(tj, f, indent=1)
+
+
+if __name__ == "__main__":
+    main(sys.argv)
