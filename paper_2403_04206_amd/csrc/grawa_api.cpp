@@ -11,20 +11,30 @@
 
 namespace {
 
-constexpr int kDefaultTileElems = 8192;
+// Norm-pass tile length: as long as possible (fewer partials, less per-block overhead) while
+// leaving at least ~8192 blocks to fill the chip; 2048 is the shortest tile that gives every lane
+// of a block one 16-byte load of bf16.
+int default_tile_elems(int K, int64_t P)
+{
+    const int64_t per_block = (int64_t)K * P / 8192;
+    int t = 16384;
+    while (t > 2048 && t > per_block) t >>= 1;
+    return t;
+}
 
 inline bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
 
 inline size_t round256(size_t n) { return (n + 255) & ~size_t(255); }
 
-int tile_elems_from_env()
+int tile_elems_for(int K, int64_t P)
 {
-    // Tuning knob: tile length in elements (multiple of 8, 256 .. 1048576).
+    // Tuning knob: GRAWA_TILE_ELEMS overrides the tile length (multiple of 8, 256 .. 1048576).
+    const int dflt = default_tile_elems(K, P);
     const char *e = std::getenv("GRAWA_TILE_ELEMS");
-    if (!e || !*e) return kDefaultTileElems;
+    if (!e || !*e) return dflt;
     char *end = nullptr;
     long v = std::strtol(e, &end, 10);
-    if (end == e || *end != '\0' || v < 256 || v > (1 << 20) || (v % 8) != 0) return kDefaultTileElems;
+    if (end == e || *end != '\0' || v < 256 || v > (1 << 20) || (v % 8) != 0) return dflt;
     return (int)v;
 }
 
@@ -160,7 +170,7 @@ grawa_status_t grawa_plan_create(grawa_plan_t **out, int K, int64_t P, int L,
 
     // Tile map: cut every layer at the multiples of T of the flat index, so tile starts are
     // either a multiple of T or a layer start and no tile crosses a layer boundary.
-    const int T = tile_elems_from_env();
+    const int T = tile_elems_for(K, P);
     std::vector<GrawaTile> tiles;
     std::vector<int32_t> layer_tile0((size_t)L + 1);
     const int64_t max_tiles = (int64_t)1 << 24; // keeps grid.x * 256 below 2^32

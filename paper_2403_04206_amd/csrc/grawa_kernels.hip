@@ -61,8 +61,8 @@ __device__ __forceinline__ double wave_min(double v)
     return v;
 }
 
-// Sum / min over the block through LDS; every thread gets the result.  `sm` holds one
-// double per wave.  Safe to call repeatedly with the same `sm`.
+// Sum over a 256-thread block through LDS; every thread gets the result.  `sm` holds one
+// double per wave.
 __device__ __forceinline__ double block_sum(double v, double *sm)
 {
     v = wave_sum(v);
@@ -72,18 +72,6 @@ __device__ __forceinline__ double block_sum(double v, double *sm)
     __syncthreads();
     double t = 0.0;
     for (int i = 0; i < GRAWA_BLOCK / GRAWA_WAVE; ++i) t += sm[i];
-    return t;
-}
-
-__device__ __forceinline__ double block_min(double v, double *sm)
-{
-    v = wave_min(v);
-    const int w = threadIdx.x / GRAWA_WAVE;
-    __syncthreads();
-    if ((threadIdx.x & (GRAWA_WAVE - 1)) == 0) sm[w] = v;
-    __syncthreads();
-    double t = sm[0];
-    for (int i = 1; i < GRAWA_BLOCK / GRAWA_WAVE; ++i) t = fmin(t, sm[i]);
     return t;
 }
 
@@ -227,26 +215,30 @@ __global__ __launch_bounds__(GRAWA_BLOCK) void k_sumsq(const GT *__restrict__ g,
 // weights
 // ---------------------------------------------------------------------------------
 
+#define GRAWA_FIN_BLOCK 1024
+#define GRAWA_FIN_WAVES (GRAWA_FIN_BLOCK / GRAWA_WAVE)
+
 // Weights of one group of K scores held in LDS (sA[k], k < K): beta_k proportional to
 // 1/A_k, summing to one, evaluated as (A_min/A_k) / sum_j (A_min/A_j) so that nothing
 // overflows.  Scores of exactly zero share the weight equally and take all of it (the
-// limit A -> 0+).  Every thread of the block must call this.
+// limit A -> 0+).  Called by ONE full wave (all 64 lanes); lanes stride over the workers.
 __device__ __forceinline__ void group_weights(const double *sA, int K, float *beta, int64_t stride,
-                                              float *beta_user, double *sm)
+                                              float *beta_user)
 {
+    const int lane = threadIdx.x & (GRAWA_WAVE - 1);
     double mn = INFINITY, nz = 0.0;
-    for (int k = threadIdx.x; k < K; k += GRAWA_BLOCK) {
+    for (int k = lane; k < K; k += GRAWA_WAVE) {
         const double a = sA[k];
         mn = fmin(mn, a);
         nz += (a == 0.0) ? 1.0 : 0.0;
     }
-    const double a_min = block_min(mn, sm);
-    const double n_zero = block_sum(nz, sm);
+    const double a_min = wave_min(mn);
+    const double n_zero = wave_sum(nz);
     double z = 0.0;
     if (n_zero == 0.0)
-        for (int k = threadIdx.x; k < K; k += GRAWA_BLOCK) z += a_min / sA[k];
-    const double zsum = block_sum(z, sm);
-    for (int k = threadIdx.x; k < K; k += GRAWA_BLOCK) {
+        for (int k = lane; k < K; k += GRAWA_WAVE) z += a_min / sA[k];
+    const double zsum = wave_sum(z);
+    for (int k = lane; k < K; k += GRAWA_WAVE) {
         const double a = sA[k];
         double b;
         if (n_zero > 0.0)
@@ -258,49 +250,84 @@ __device__ __forceinline__ void group_weights(const double *sA, int K, float *be
     }
 }
 
-// grid L, block 256.  Block l adds the tile partials of layer l for every worker (one wave
-// per worker at a time, lanes striding over the layer's tiles), then turns the K layer
-// norms into the K per-layer weights.
-__global__ __launch_bounds__(GRAWA_BLOCK) void k_finalize_layers(
+// Sum of p[t0 + first], p[t0 + first + step], ... below t1 over the lanes of one wave, four
+// independent loads in flight per lane; every lane gets the total.
+__device__ __forceinline__ double wave_strided_sum(const double *__restrict__ p, int t0, int t1, int first,
+                                                   int step)
+{
+    double s0 = 0.0, s1 = 0.0, s2 = 0.0, s3 = 0.0;
+    int t = t0 + first;
+    for (; t + 3 * step < t1; t += 4 * step) {
+        s0 += p[t];
+        s1 += p[t + step];
+        s2 += p[t + 2 * step];
+        s3 += p[t + 3 * step];
+    }
+    for (; t < t1; t += step) s0 += p[t];
+    return wave_sum((s0 + s1) + (s2 + s3));
+}
+
+// grid L, block 1024 (16 waves).  Block l adds the tile partials of layer l for every worker
+// and turns the K layer norms into the K per-layer weights.  With K >= 16 every wave takes
+// workers w, w+16, ...; with fewer workers 16/K waves share one worker's tiles and their
+// results are added in wave order.  All sums are fp64 in a fixed order (no atomics).
+__global__ __launch_bounds__(GRAWA_FIN_BLOCK) void k_finalize_layers(
     const double *__restrict__ partials, int64_t n_tiles, const int32_t *__restrict__ layer_tile0,
     int K, int L, double *__restrict__ S, float *__restrict__ A, float *__restrict__ A_user,
     float *__restrict__ beta, float *__restrict__ beta_user)
 {
     __shared__ double sA[GRAWA_MAX_WORKERS];
-    __shared__ double sm[GRAWA_BLOCK / GRAWA_WAVE];
+    __shared__ double sw[GRAWA_FIN_WAVES];
     const int l = blockIdx.x;
     const int t0 = layer_tile0[l], t1 = layer_tile0[l + 1];
     const int lane = threadIdx.x & (GRAWA_WAVE - 1);
     const int wave = threadIdx.x / GRAWA_WAVE;
-    for (int k = wave; k < K; k += GRAWA_BLOCK / GRAWA_WAVE) {
-        const double *p = partials + (int64_t)k * n_tiles;
-        double s = 0.0;
-        for (int t = t0 + lane; t < t1; t += GRAWA_WAVE) s += p[t];
-        s = wave_sum(s);
-        if (lane == 0) {
-            const double a = sqrt(s);
-            S[(int64_t)k * L + l] = s;
-            A[(int64_t)k * L + l] = (float)a;
-            if (A_user) A_user[(int64_t)k * L + l] = (float)a;
-            sA[k] = a;
+    if (K >= GRAWA_FIN_WAVES) {
+        for (int k = wave; k < K; k += GRAWA_FIN_WAVES) {
+            const double s = wave_strided_sum(partials + (int64_t)k * n_tiles, t0, t1, lane, GRAWA_WAVE);
+            if (lane == 0) sA[k] = s;
         }
+        __syncthreads();
+    } else {
+        const int share = GRAWA_FIN_WAVES / K; // waves per worker
+        const int k = wave % K, part = wave / K;
+        double s = 0.0;
+        if (part < share)
+            s = wave_strided_sum(partials + (int64_t)k * n_tiles, t0, t1, part * GRAWA_WAVE + lane,
+                                 share * GRAWA_WAVE);
+        if (lane == 0) sw[wave] = s;
+        __syncthreads();
+        if (threadIdx.x < K) {
+            double tot = 0.0;
+            for (int j = 0; j < share; ++j) tot += sw[threadIdx.x + j * K];
+            sA[threadIdx.x] = tot;
+        }
+        __syncthreads();
+    }
+    // sA[k] holds the squared norm; publish it, replace it by the norm, then the weights
+    for (int k = threadIdx.x; k < K; k += GRAWA_FIN_BLOCK) {
+        const double s = sA[k];
+        const double a = sqrt(s);
+        S[(int64_t)k * L + l] = s;
+        A[(int64_t)k * L + l] = (float)a;
+        if (A_user) A_user[(int64_t)k * L + l] = (float)a;
+        sA[k] = a;
     }
     __syncthreads();
-    group_weights(sA, K, beta + l, L, beta_user ? beta_user + l : nullptr, sm);
+    if (wave == 0) group_weights(sA, K, beta + l, L, beta_user ? beta_user + l : nullptr);
 }
 
-// grid 1, block 256.  Model-level score per worker from the [K][L] squared layer norms:
+// grid 1, block 1024.  Model-level score per worker from the [K][L] squared layer norms:
 // mode 0: sum of the layer norms; mode 1: norm of the flattened gradient.  Then the K weights.
-__global__ __launch_bounds__(GRAWA_BLOCK) void k_finalize_model(const double *__restrict__ S, int K,
-                                                                int L, int mode,
-                                                                float *__restrict__ beta,
-                                                                float *__restrict__ beta_user)
+__global__ __launch_bounds__(GRAWA_FIN_BLOCK) void k_finalize_model(const double *__restrict__ S, int K,
+                                                                    int L, int mode,
+                                                                    float *__restrict__ beta,
+                                                                    float *__restrict__ beta_user)
 {
     __shared__ double sA[GRAWA_MAX_WORKERS];
-    __shared__ double sm[GRAWA_BLOCK / GRAWA_WAVE];
     const int lane = threadIdx.x & (GRAWA_WAVE - 1);
     const int wave = threadIdx.x / GRAWA_WAVE;
-    for (int k = wave; k < K; k += GRAWA_BLOCK / GRAWA_WAVE) {
+    for (int k = wave; k < K; k += GRAWA_FIN_WAVES) {
         const double *p = S + (int64_t)k * L;
         double s = 0.0;
         if (mode == GRAWA_NORM_LAYERSUM)
@@ -312,7 +339,7 @@ __global__ __launch_bounds__(GRAWA_BLOCK) void k_finalize_model(const double *__
         if (lane == 0) sA[k] = s;
     }
     __syncthreads();
-    group_weights(sA, K, beta, 1, beta_user, sm);
+    if (wave == 0) group_weights(sA, K, beta, 1, beta_user);
 }
 
 // ---------------------------------------------------------------------------------
@@ -339,8 +366,11 @@ __device__ __forceinline__ int layer_of(const int64_t *__restrict__ off, int lay
 // loads); < 0: the block contains a layer boundary, ~cell_layer[m] is the layer of its first
 // column and each lane finds its own layer.  Model-level weights pass cell_layer = nullptr.
 // The pull is x + lambda (c - x), one fma, which leaves a single worker exactly unchanged.
-template <int KT, bool EXACT, bool SGD, typename GT, bool NT>
-__global__ __launch_bounds__(GRAWA_CELL) void k_center_pull(
+// WPE caps the waves per SIMD: the pass is fastest with roughly 32-48 row loads in flight per
+// SIMD (K x WPE); more only queues requests to K far-apart rows and costs DRAM efficiency
+// (measured: K = 16 at 3 waves 6.1 TB/s, at 8 waves 5.7; K = 8 at 4 waves 6.5, at 8 waves 6.2).
+template <int KT, bool EXACT, bool SGD, typename GT, bool NT, int WPE>
+__global__ __launch_bounds__(GRAWA_CELL) __attribute__((amdgpu_waves_per_eu(1, WPE))) void k_center_pull(
     float *__restrict__ x, int64_t ldx, const GT *__restrict__ g, int64_t ldg, float lr,
     const float *__restrict__ beta, int64_t beta_stride, const int32_t *__restrict__ cell_layer,
     const int64_t *__restrict__ off, int L, int K, int64_t P, float lambda,
@@ -475,7 +505,7 @@ hipError_t grawa_launch_sumsq(const grawa_plan *p, const void *g, int64_t ldg, g
 hipError_t grawa_launch_finalize_layers(const grawa_plan *p, float *norms_user, float *beta_user,
                                         hipStream_t s)
 {
-    k_finalize_layers<<<dim3((unsigned)p->L), dim3(GRAWA_BLOCK), 0, s>>>(
+    k_finalize_layers<<<dim3((unsigned)p->L), dim3(GRAWA_FIN_BLOCK), 0, s>>>(
         p->d_partials, p->n_tiles, p->d_layer_tile0, p->K, p->L, p->d_S, p->d_A, norms_user,
         p->d_beta_layer, beta_user);
     return hipGetLastError();
@@ -484,16 +514,24 @@ hipError_t grawa_launch_finalize_layers(const grawa_plan *p, float *norms_user, 
 hipError_t grawa_launch_finalize_model(const grawa_plan *p, grawa_norm_mode_t mode, float *beta_user,
                                        hipStream_t s)
 {
-    k_finalize_model<<<dim3(1), dim3(GRAWA_BLOCK), 0, s>>>(p->d_S, p->K, p->L, (int)mode,
+    k_finalize_model<<<dim3(1), dim3(GRAWA_FIN_BLOCK), 0, s>>>(p->d_S, p->K, p->L, (int)mode,
                                                           p->d_beta_model, beta_user);
     return hipGetLastError();
+}
+
+// Waves per SIMD the center+pull kernel is capped at, from a sweep of this kernel over K and
+// the cap on the part (best throughput at roughly 32-48 row loads in flight per SIMD).
+constexpr int grawa_waves_for(int k, bool sgd)
+{
+    if (sgd) return k <= 2 ? 8 : k == 3 ? 6 : k <= 5 ? 5 : k <= 7 ? 4 : k <= 11 ? 3 : 2;
+    return k <= 4 ? 8 : k == 5 ? 6 : k <= 7 ? 5 : k <= 10 ? 4 : k <= 20 ? 3 : k <= 28 ? 2 : 1;
 }
 
 template <int KT, bool EXACT, bool SGD, typename GT, bool NT>
 static void launch_cp(const grawa_plan *p, float *x, int64_t ldx, const void *g, int64_t ldg, float lr,
                       const float *beta, int per_layer, float lambda, float *center_out, hipStream_t s)
 {
-    k_center_pull<KT, EXACT, SGD, GT, NT><<<dim3((unsigned)p->n_cells), dim3(GRAWA_CELL), 0, s>>>(
+    k_center_pull<KT, EXACT, SGD, GT, NT, grawa_waves_for(KT, SGD)><<<dim3((unsigned)p->n_cells), dim3(GRAWA_CELL), 0, s>>>(
         x, ldx, (const GT *)g, ldg, lr, beta, per_layer ? (int64_t)p->L : 1,
         per_layer ? p->d_cell_layer : nullptr, p->d_off, p->L, p->K, p->P, lambda, center_out);
 }
@@ -525,6 +563,8 @@ static void dispatch_cp(const grawa_plan *p, float *x, int64_t ldx, const void *
 #undef GRAWA_CP_CASE
 }
 
+#define GRAWA_STREAMING_MIN_BYTES ((int64_t)512 << 20)
+
 // Streaming accesses are used only when no cache line is shared between two rows or written
 // in two parts: base pointers and row pitches are multiples of 128 bytes.
 static bool rows_line_aligned(const void *base, int64_t ld, int elem_bytes)
@@ -537,7 +577,9 @@ hipError_t grawa_launch_center_pull(const grawa_plan *p, float *x, int64_t ldx, 
                                     grawa_dtype_t dt, float lr, int fuse_sgd, float *center_out,
                                     hipStream_t s)
 {
-    bool nt = rows_line_aligned(x, ldx, 4) && (!center_out || rows_line_aligned(center_out, 0, 4));
+    // Streaming accesses pay off only when the arrays do not fit the last-level cache anyway.
+    bool nt = (int64_t)p->K * p->P * 4 > GRAWA_STREAMING_MIN_BYTES && rows_line_aligned(x, ldx, 4) &&
+              (!center_out || rows_line_aligned(center_out, 0, 4));
     if (fuse_sgd) nt = nt && rows_line_aligned(g_sgd, ldg_sgd, dt == GRAWA_BF16 ? 2 : 4);
     if (!fuse_sgd) {
         if (nt) dispatch_cp<false, float, true>(p, x, ldx, nullptr, 0, 0.f, beta, per_layer, lambda, center_out, s);
@@ -557,7 +599,8 @@ hipError_t grawa_launch_local_sgd(float *x, int64_t ldx, const void *g, int64_t 
 {
     const int64_t gx = (P + GRAWA_CELL - 1) / GRAWA_CELL;
     const dim3 grid((unsigned)gx, (unsigned)K), block(GRAWA_CELL);
-    const bool nt = rows_line_aligned(x, ldx, 4) && rows_line_aligned(g, ldg, dt == GRAWA_BF16 ? 2 : 4);
+    const bool nt = (int64_t)K * P * 4 > GRAWA_STREAMING_MIN_BYTES && rows_line_aligned(x, ldx, 4) &&
+                    rows_line_aligned(g, ldg, dt == GRAWA_BF16 ? 2 : 4);
     if (dt == GRAWA_BF16) {
         if (nt) k_local_sgd<uint16_t, true><<<grid, block, 0, s>>>(x, ldx, (const uint16_t *)g, ldg, P, lr);
         else k_local_sgd<uint16_t, false><<<grid, block, 0, s>>>(x, ldx, (const uint16_t *)g, ldg, P, lr);
