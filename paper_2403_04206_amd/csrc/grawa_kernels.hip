@@ -75,7 +75,8 @@ __device__ __forceinline__ double block_sum(double v, double *sm)
     return t;
 }
 
-typedef float v4f __attribute__((ext_vector_type(4)));
+typedef float v2f __attribute__((ext_vector_type(2)));
+typedef unsigned int v2u __attribute__((ext_vector_type(2)));
 typedef unsigned int v4u __attribute__((ext_vector_type(4)));
 
 // Global-memory accessors for the one-element-per-lane kernels.  An address is a wave-uniform
@@ -107,47 +108,50 @@ template <bool NT, typename T> __device__ __forceinline__ void st_lane(uint64_t 
     else *p = v;
 }
 
-// Gradient element access.  VEC16 = elements per 16-byte load (norm pass).
+// Gradient element access.  VEC8 = elements per 8-byte load (norm pass).
 template <typename GT> struct Grad;
 
 template <> struct Grad<float> {
-    static constexpr int VEC16 = 4;
+    static constexpr int VEC8 = 2;
     static __device__ __forceinline__ float one(const float *p) { return *p; }
     template <bool NT> static __device__ __forceinline__ float lane(uint64_t base, unsigned off)
     {
         return ld_lane<NT, float>(base, off);
     }
-    // acc + sum of squares of the 4 floats at p (16-byte aligned), streaming load
-    static __device__ __forceinline__ float sumsq16(const float *p, float acc)
+    // 8 bytes (2 floats) at p, 8-byte aligned, streaming load; and their squares added to acc
+    typedef v2f Vec8;
+    static __device__ __forceinline__ Vec8 load8(const float *p)
     {
-        const v4f q = __builtin_nontemporal_load(reinterpret_cast<const v4f *>(p));
+        return __builtin_nontemporal_load(reinterpret_cast<const v2f *>(p));
+    }
+    static __device__ __forceinline__ float sumsq8(Vec8 q, float acc)
+    {
         acc = fmaf(q.x, q.x, acc);
         acc = fmaf(q.y, q.y, acc);
-        acc = fmaf(q.z, q.z, acc);
-        acc = fmaf(q.w, q.w, acc);
         return acc;
     }
 };
 
 template <> struct Grad<uint16_t> { // bfloat16 bit patterns
-    static constexpr int VEC16 = 8;
+    static constexpr int VEC8 = 4;
     static __device__ __forceinline__ float one(const uint16_t *p) { return bf16_one(*p); }
     template <bool NT> static __device__ __forceinline__ float lane(uint64_t base, unsigned off)
     {
         return bf16_one(ld_lane<NT, uint16_t>(base, off));
     }
-    static __device__ __forceinline__ float sumsq16(const uint16_t *p, float acc)
+    // 8 bytes (4 bf16) at p, 8-byte aligned, streaming load; and their squares added to acc
+    typedef v2u Vec8;
+    static __device__ __forceinline__ Vec8 load8(const uint16_t *p)
     {
-        const v4u q = __builtin_nontemporal_load(reinterpret_cast<const v4u *>(p));
+        return __builtin_nontemporal_load(reinterpret_cast<const v2u *>(p));
+    }
+    static __device__ __forceinline__ float sumsq8(Vec8 q, float acc)
+    {
         float a;
         a = bf16_lo(q.x); acc = fmaf(a, a, acc);
         a = bf16_hi(q.x); acc = fmaf(a, a, acc);
         a = bf16_lo(q.y); acc = fmaf(a, a, acc);
         a = bf16_hi(q.y); acc = fmaf(a, a, acc);
-        a = bf16_lo(q.z); acc = fmaf(a, a, acc);
-        a = bf16_hi(q.z); acc = fmaf(a, a, acc);
-        a = bf16_lo(q.w); acc = fmaf(a, a, acc);
-        a = bf16_hi(q.w); acc = fmaf(a, a, acc);
         return acc;
     }
 };
@@ -157,17 +161,18 @@ template <> struct Grad<uint16_t> { // bfloat16 bit patterns
 // ---------------------------------------------------------------------------------
 
 // grid (n_tiles, K), block 256.  partials[k][tile] = sum over the tile of g[k][i]^2.
-// Each lane issues up to 8 independent 16-byte streaming loads per trip and keeps one fp32
-// accumulator per load, so an accumulator chain is at most tile_elems/256/8 vectors long
-// (one vector for the default tile); everything after the lane is fp64.
+// Each lane issues 8 independent 8-byte streaming loads per trip and keeps one fp32
+// accumulator per load; with the occupancy capped at 4 waves per SIMD this shape measured
+// fastest for a read-only stream on this part (7.3-7.4 TB/s; 16-byte loads at full occupancy
+// 6.9-7.0).  An accumulator chain is tile_elems/256/8 elements long (8 for the longest tile);
+// everything after the lane is fp64.
 #define GRAWA_SUMSQ_U 8
 template <typename GT>
-__global__ __launch_bounds__(GRAWA_BLOCK) void k_sumsq(const GT *__restrict__ g, int64_t ldg,
-                                                       const GrawaTile *__restrict__ tiles,
-                                                       int64_t n_tiles,
-                                                       double *__restrict__ partials)
+__global__ __launch_bounds__(GRAWA_BLOCK) __attribute__((amdgpu_waves_per_eu(1, 4))) void k_sumsq(
+    const GT *__restrict__ g, int64_t ldg, const GrawaTile *__restrict__ tiles, int64_t n_tiles,
+    double *__restrict__ partials)
 {
-    constexpr int V = Grad<GT>::VEC16;
+    constexpr int V = Grad<GT>::VEC8;
     const GrawaTile t = tiles[blockIdx.x];
     const int k = blockIdx.y;
     const GT *row = g + (int64_t)k * ldg;
@@ -193,13 +198,30 @@ __global__ __launch_bounds__(GRAWA_BLOCK) void k_sumsq(const GT *__restrict__ g,
         acc[1] = v * v;
     }
 
+    // Body: all loads of a trip are issued before any is used.  Full trips need no bounds
+    // checks; the last, partial trip loads a clamped (valid) address and discards the value.
     const int nvec = (int)((b_al - a_al) / V);
     const GT *body = row + a_al;
-    for (int j0 = tid; j0 < nvec; j0 += GRAWA_SUMSQ_U * GRAWA_BLOCK) {
+    typename Grad<GT>::Vec8 q[GRAWA_SUMSQ_U];
+    int j0 = tid;
+    for (; j0 + (GRAWA_SUMSQ_U - 1) * GRAWA_BLOCK < nvec; j0 += GRAWA_SUMSQ_U * GRAWA_BLOCK) {
+#pragma unroll
+        for (int u = 0; u < GRAWA_SUMSQ_U; ++u) q[u] = Grad<GT>::load8(body + (int64_t)(j0 + u * GRAWA_BLOCK) * V);
+        __builtin_amdgcn_sched_barrier(0); // keep the arithmetic from being hoisted between the loads
+#pragma unroll
+        for (int u = 0; u < GRAWA_SUMSQ_U; ++u) acc[u] = Grad<GT>::sumsq8(q[u], acc[u]);
+    }
+    if (j0 < nvec) {
 #pragma unroll
         for (int u = 0; u < GRAWA_SUMSQ_U; ++u) {
             const int j = j0 + u * GRAWA_BLOCK;
-            if (j < nvec) acc[u] = Grad<GT>::sumsq16(body + (int64_t)j * V, acc[u]);
+            q[u] = Grad<GT>::load8(body + (int64_t)(j < nvec ? j : j0) * V);
+        }
+        __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+        for (int u = 0; u < GRAWA_SUMSQ_U; ++u) {
+            const float r = Grad<GT>::sumsq8(q[u], 0.f);
+            acc[u] += (j0 + u * GRAWA_BLOCK < nvec) ? r : 0.f;
         }
     }
 
