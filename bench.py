@@ -10,8 +10,9 @@ Prints ONE JSON line.  `value` is the update's HBM bandwidth under the minimum-t
 model (bytes every correct implementation must move: gradients read once for the norms,
 parameters read once and written once, gradients read a second time when the SGD step is
 fused) divided by the measured time per step.  `roofline` is the same kind of figure for the
-dominant kernel alone (center+pull), from HIP events recorded around that kernel inside the
-timed steps.  `cpu_baseline` is the float64 CPU reference timed on a bounded sample of the
+dominant kernel alone (center+pull), from HIP start/stop events attached to that kernel's
+launches while the timed steps are repeated once more (so that `value` carries no event
+overhead).  `cpu_baseline` is the float64 CPU reference timed on a bounded sample of the
 same workload on this machine's host cores.
 """
 import argparse
@@ -71,13 +72,18 @@ def time_config(torch, grawa, W, idx, variant, steps, warmup):
         info = plan.info()
         for _ in range(warmup):
             call_update(plan, w, x, g, variant)
+        # timed region: exactly `steps` updates, bracketed by device synchronisation
         torch.cuda.synchronize()
-        plan.profile(True)
         t0 = time.perf_counter()
         for _ in range(steps):
             call_update(plan, w, x, g, variant)
         torch.cuda.synchronize()
         t1 = time.perf_counter()
+        # the same steps again with start/stop events attached to the two big kernels
+        plan.profile(True)
+        for _ in range(steps):
+            call_update(plan, w, x, g, variant)
+        torch.cuda.synchronize()
         prof = plan.profile_read()
         plan.profile(False)
     ms = (t1 - t0) * 1e3 / steps

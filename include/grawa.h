@@ -159,10 +159,12 @@ grawa_status_t grawa_lgrawa_update_sgd(grawa_plan_t *plan, float *x, int64_t ldx
 /*
  * Measurement aids (not part of the method).
  *
- * grawa_plan_profile: with enable != 0 the plan records a pair of HIP events
- * around the gradient-norm kernel and around the center+pull kernel of every
- * later update call (up to 4096 calls, then it stops recording).  With
- * enable == 0 recording stops.  Either way the counters are reset.
+ * grawa_plan_profile: with enable != 0 the plan attaches a start and a stop
+ * HIP event to the launch of the gradient-norm kernel and of the center+pull
+ * kernel of every later update call (the events time the dispatch itself and
+ * queue nothing extra on the stream; up to 4096 calls, then it stops
+ * recording).  With enable == 0 recording stops.  Either way the counters are
+ * reset.
  *
  * grawa_plan_profile_read: the caller must have synchronised the stream.
  * Returns the number of recorded calls in *n_calls and the summed durations in

@@ -113,21 +113,15 @@ grawa_status_t run_update(grawa_plan *p, float *x, int64_t ldx, const void *g, i
     const bool prof = prof_active(p);
     hipEvent_t *ev = prof ? p->ev + 4 * (size_t)p->profile_n : nullptr;
 
-    if (prof) GRAWA_TRY_HIP(hipEventRecord(ev[0], s));
-    GRAWA_TRY_HIP(grawa_launch_sumsq(p, g, ldg, dt, s));
-    if (prof) GRAWA_TRY_HIP(hipEventRecord(ev[1], s));
+    GRAWA_TRY_HIP(grawa_launch_sumsq(p, g, ldg, dt, s, prof ? ev[0] : nullptr, prof ? ev[1] : nullptr));
 
     GRAWA_TRY_HIP(grawa_launch_finalize_layers(p, nullptr, per_layer ? weights_out : nullptr, s));
     if (!per_layer) GRAWA_TRY_HIP(grawa_launch_finalize_model(p, mode, weights_out, s));
 
-    if (prof) GRAWA_TRY_HIP(hipEventRecord(ev[2], s));
     GRAWA_TRY_HIP(grawa_launch_center_pull(p, x, ldx, per_layer ? p->d_beta_layer : p->d_beta_model,
                                            per_layer, lambda, g_sgd, ldg_sgd, dt, lr, fuse_sgd,
-                                           center_out, s));
-    if (prof) {
-        GRAWA_TRY_HIP(hipEventRecord(ev[3], s));
-        p->profile_n += 1;
-    }
+                                           center_out, s, prof ? ev[2] : nullptr, prof ? ev[3] : nullptr));
+    if (prof) p->profile_n += 1;
     return GRAWA_OK;
 }
 
@@ -289,7 +283,7 @@ grawa_status_t grawa_grad_norms(grawa_plan_t *p, const void *g, int64_t ldg, gra
     DeviceGuard guard(p->device);
     if (!guard.ok) return GRAWA_ERR_HIP;
     hipStream_t s = static_cast<hipStream_t>(stream);
-    GRAWA_TRY_HIP(grawa_launch_sumsq(p, g, ldg, dt, s));
+    GRAWA_TRY_HIP(grawa_launch_sumsq(p, g, ldg, dt, s, nullptr, nullptr));
     GRAWA_TRY_HIP(grawa_launch_finalize_layers(p, norms_out, nullptr, s));
     return GRAWA_OK;
 }
@@ -340,15 +334,10 @@ grawa_status_t grawa_center_pull(grawa_plan_t *p, float *x, int64_t ldx, const f
     hipStream_t s = static_cast<hipStream_t>(stream);
     const bool prof = prof_active(p);
     hipEvent_t *ev = prof ? p->ev + 4 * (size_t)p->profile_n : nullptr;
-    if (prof) {
-        GRAWA_TRY_HIP(hipEventRecord(ev[0], s));
-        GRAWA_TRY_HIP(hipEventRecord(ev[1], s));
-        GRAWA_TRY_HIP(hipEventRecord(ev[2], s));
-    }
     GRAWA_TRY_HIP(grawa_launch_center_pull(p, x, ldx, weights, per_layer ? 1 : 0, lambda, nullptr, 0, GRAWA_F32,
-                                           0.f, 0, center_out, s));
+                                           0.f, 0, center_out, s, prof ? ev[2] : nullptr, prof ? ev[3] : nullptr));
     if (prof) {
-        GRAWA_TRY_HIP(hipEventRecord(ev[3], s));
+        p->profile_pull_only = 1;
         p->profile_n += 1;
     }
     return GRAWA_OK;
@@ -380,6 +369,7 @@ grawa_status_t grawa_plan_profile(grawa_plan_t *p, int enable)
     }
     p->profile_on = enable ? 1 : 0;
     p->profile_n = 0;
+    p->profile_pull_only = 0;
     return GRAWA_OK;
 }
 
@@ -389,8 +379,10 @@ grawa_status_t grawa_plan_profile_read(grawa_plan_t *p, int *n_calls, double *no
     double a = 0.0, b = 0.0;
     for (int i = 0; i < p->profile_n; ++i) {
         float ms = 0.f;
-        GRAWA_TRY_HIP(hipEventElapsedTime(&ms, p->ev[4 * i + 0], p->ev[4 * i + 1]));
-        a += ms;
+        if (!p->profile_pull_only) {
+            GRAWA_TRY_HIP(hipEventElapsedTime(&ms, p->ev[4 * i + 0], p->ev[4 * i + 1]));
+            a += ms;
+        }
         GRAWA_TRY_HIP(hipEventElapsedTime(&ms, p->ev[4 * i + 2], p->ev[4 * i + 3]));
         b += ms;
     }

@@ -41,12 +41,14 @@ struct grawa_plan {
     // measurement aid
     int profile_on;
     int profile_n;
+    int profile_pull_only; // set when grawa_center_pull was profiled (no norm-kernel events)
     hipEvent_t *ev; // 4 per slot: norm begin/end, pull begin/end
 };
 
 // Launchers (defined in grawa_kernels.hip).  All return the hipError_t of the launch.
+// e0/e1: optional start/stop events of the launch itself (null when not profiling).
 hipError_t grawa_launch_sumsq(const grawa_plan *p, const void *g, int64_t ldg, grawa_dtype_t dt,
-                              hipStream_t s);
+                              hipStream_t s, hipEvent_t e0, hipEvent_t e1);
 hipError_t grawa_launch_finalize_layers(const grawa_plan *p, float *norms_user, float *beta_user,
                                         hipStream_t s);
 hipError_t grawa_launch_finalize_model(const grawa_plan *p, grawa_norm_mode_t mode, float *beta_user,
@@ -54,7 +56,7 @@ hipError_t grawa_launch_finalize_model(const grawa_plan *p, grawa_norm_mode_t mo
 hipError_t grawa_launch_center_pull(const grawa_plan *p, float *x, int64_t ldx, const float *beta,
                                     int per_layer, float lambda, const void *g_sgd,
                                     int64_t ldg_sgd, grawa_dtype_t dt, float lr, int fuse_sgd,
-                                    float *center_out, hipStream_t s);
+                                    float *center_out, hipStream_t s, hipEvent_t e0, hipEvent_t e1);
 hipError_t grawa_launch_local_sgd(float *x, int64_t ldx, const void *g, int64_t ldg,
                                   grawa_dtype_t dt, int K, int64_t P, float lr, hipStream_t s);
 hipError_t grawa_launch_stream_copy(void *dst, const void *src, int64_t nbytes, hipStream_t s);

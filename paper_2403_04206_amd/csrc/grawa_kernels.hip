@@ -19,6 +19,8 @@
 //                      local SGD step x_k - lr g_k optionally applied on the way in
 //                                                   [display after eq. (2); Alg. 1, 2]
 //   k_local_sgd        x_k <- x_k - lr g_k                                 [Alg. 1, 2]
+#include <hip/hip_ext.h>
+
 #include "grawa_internal.h"
 
 #define GRAWA_BLOCK 256
@@ -513,14 +515,18 @@ __global__ __launch_bounds__(GRAWA_COPY_BLOCK) void k_stream_copy(v4u *__restric
 // launchers
 // ---------------------------------------------------------------------------------
 
+// Kernels that are timed carry their own start/stop events (taken from the dispatch itself,
+// so nothing extra is queued on the stream); both may be null.
 hipError_t grawa_launch_sumsq(const grawa_plan *p, const void *g, int64_t ldg, grawa_dtype_t dt,
-                              hipStream_t s)
+                              hipStream_t s, hipEvent_t e0, hipEvent_t e1)
 {
     const dim3 grid((unsigned)p->n_tiles, (unsigned)p->K), block(GRAWA_BLOCK);
     if (dt == GRAWA_BF16)
-        k_sumsq<uint16_t><<<grid, block, 0, s>>>((const uint16_t *)g, ldg, p->d_tiles, p->n_tiles, p->d_partials);
+        hipExtLaunchKernelGGL(k_sumsq<uint16_t>, grid, block, 0, s, e0, e1, 0, (const uint16_t *)g, ldg,
+                              (const GrawaTile *)p->d_tiles, p->n_tiles, p->d_partials);
     else
-        k_sumsq<float><<<grid, block, 0, s>>>((const float *)g, ldg, p->d_tiles, p->n_tiles, p->d_partials);
+        hipExtLaunchKernelGGL(k_sumsq<float>, grid, block, 0, s, e0, e1, 0, (const float *)g, ldg,
+                              (const GrawaTile *)p->d_tiles, p->n_tiles, p->d_partials);
     return hipGetLastError();
 }
 
@@ -551,21 +557,25 @@ constexpr int grawa_waves_for(int k, bool sgd)
 
 template <int KT, bool EXACT, bool SGD, typename GT, bool NT>
 static void launch_cp(const grawa_plan *p, float *x, int64_t ldx, const void *g, int64_t ldg, float lr,
-                      const float *beta, int per_layer, float lambda, float *center_out, hipStream_t s)
+                      const float *beta, int per_layer, float lambda, float *center_out, hipStream_t s,
+                      hipEvent_t e0, hipEvent_t e1)
 {
-    k_center_pull<KT, EXACT, SGD, GT, NT, grawa_waves_for(KT, SGD)><<<dim3((unsigned)p->n_cells), dim3(GRAWA_CELL), 0, s>>>(
-        x, ldx, (const GT *)g, ldg, lr, beta, per_layer ? (int64_t)p->L : 1,
-        per_layer ? p->d_cell_layer : nullptr, p->d_off, p->L, p->K, p->P, lambda, center_out);
+    hipExtLaunchKernelGGL((k_center_pull<KT, EXACT, SGD, GT, NT, grawa_waves_for(KT, SGD)>),
+                          dim3((unsigned)p->n_cells), dim3(GRAWA_CELL), 0, s, e0, e1, 0, x, ldx, (const GT *)g, ldg,
+                          lr, beta, per_layer ? (int64_t)p->L : (int64_t)1,
+                          per_layer ? (const int32_t *)p->d_cell_layer : (const int32_t *)nullptr,
+                          (const int64_t *)p->d_off, p->L, p->K, p->P, lambda, center_out);
 }
 
 // One kernel per worker count up to 32 (fully unrolled, no guards); 33..64 workers share a
 // guarded 64-slot kernel; beyond that the two-sweep kernel.
 template <bool SGD, typename GT, bool NT>
 static void dispatch_cp(const grawa_plan *p, float *x, int64_t ldx, const void *g, int64_t ldg, float lr,
-                        const float *beta, int per_layer, float lambda, float *center_out, hipStream_t s)
+                        const float *beta, int per_layer, float lambda, float *center_out, hipStream_t s,
+                        hipEvent_t e0, hipEvent_t e1)
 {
 #define GRAWA_CP_CASE(N) \
-    case N: launch_cp<N, true, SGD, GT, NT>(p, x, ldx, g, ldg, lr, beta, per_layer, lambda, center_out, s); break;
+    case N: launch_cp<N, true, SGD, GT, NT>(p, x, ldx, g, ldg, lr, beta, per_layer, lambda, center_out, s, e0, e1); break;
     const int K = p->K;
     switch (K) {
         GRAWA_CP_CASE(1) GRAWA_CP_CASE(2) GRAWA_CP_CASE(3) GRAWA_CP_CASE(4) GRAWA_CP_CASE(5) GRAWA_CP_CASE(6)
@@ -576,11 +586,13 @@ static void dispatch_cp(const grawa_plan *p, float *x, int64_t ldx, const void *
         GRAWA_CP_CASE(31) GRAWA_CP_CASE(32)
     default:
         if (K <= 64)
-            launch_cp<64, false, SGD, GT, NT>(p, x, ldx, g, ldg, lr, beta, per_layer, lambda, center_out, s);
+            launch_cp<64, false, SGD, GT, NT>(p, x, ldx, g, ldg, lr, beta, per_layer, lambda, center_out, s, e0, e1);
         else
-            k_center_pull_any<SGD, GT><<<dim3((unsigned)p->n_cells), dim3(GRAWA_CELL), 0, s>>>(
-                x, ldx, (const GT *)g, ldg, lr, beta, per_layer ? (int64_t)p->L : 1,
-                per_layer ? p->d_cell_layer : nullptr, p->d_off, p->L, K, p->P, lambda, center_out);
+            hipExtLaunchKernelGGL((k_center_pull_any<SGD, GT>), dim3((unsigned)p->n_cells), dim3(GRAWA_CELL), 0, s,
+                                  e0, e1, 0, x, ldx, (const GT *)g, ldg, lr, beta,
+                                  per_layer ? (int64_t)p->L : (int64_t)1,
+                                  per_layer ? (const int32_t *)p->d_cell_layer : (const int32_t *)nullptr,
+                                  (const int64_t *)p->d_off, p->L, K, p->P, lambda, center_out);
     }
 #undef GRAWA_CP_CASE
 }
@@ -597,21 +609,21 @@ static bool rows_line_aligned(const void *base, int64_t ld, int elem_bytes)
 hipError_t grawa_launch_center_pull(const grawa_plan *p, float *x, int64_t ldx, const float *beta,
                                     int per_layer, float lambda, const void *g_sgd, int64_t ldg_sgd,
                                     grawa_dtype_t dt, float lr, int fuse_sgd, float *center_out,
-                                    hipStream_t s)
+                                    hipStream_t s, hipEvent_t e0, hipEvent_t e1)
 {
     // Streaming accesses pay off only when the arrays do not fit the last-level cache anyway.
     bool nt = (int64_t)p->K * p->P * 4 > GRAWA_STREAMING_MIN_BYTES && rows_line_aligned(x, ldx, 4) &&
               (!center_out || rows_line_aligned(center_out, 0, 4));
     if (fuse_sgd) nt = nt && rows_line_aligned(g_sgd, ldg_sgd, dt == GRAWA_BF16 ? 2 : 4);
     if (!fuse_sgd) {
-        if (nt) dispatch_cp<false, float, true>(p, x, ldx, nullptr, 0, 0.f, beta, per_layer, lambda, center_out, s);
-        else dispatch_cp<false, float, false>(p, x, ldx, nullptr, 0, 0.f, beta, per_layer, lambda, center_out, s);
+        if (nt) dispatch_cp<false, float, true>(p, x, ldx, nullptr, 0, 0.f, beta, per_layer, lambda, center_out, s, e0, e1);
+        else dispatch_cp<false, float, false>(p, x, ldx, nullptr, 0, 0.f, beta, per_layer, lambda, center_out, s, e0, e1);
     } else if (dt == GRAWA_BF16) {
-        if (nt) dispatch_cp<true, uint16_t, true>(p, x, ldx, g_sgd, ldg_sgd, lr, beta, per_layer, lambda, center_out, s);
-        else dispatch_cp<true, uint16_t, false>(p, x, ldx, g_sgd, ldg_sgd, lr, beta, per_layer, lambda, center_out, s);
+        if (nt) dispatch_cp<true, uint16_t, true>(p, x, ldx, g_sgd, ldg_sgd, lr, beta, per_layer, lambda, center_out, s, e0, e1);
+        else dispatch_cp<true, uint16_t, false>(p, x, ldx, g_sgd, ldg_sgd, lr, beta, per_layer, lambda, center_out, s, e0, e1);
     } else {
-        if (nt) dispatch_cp<true, float, true>(p, x, ldx, g_sgd, ldg_sgd, lr, beta, per_layer, lambda, center_out, s);
-        else dispatch_cp<true, float, false>(p, x, ldx, g_sgd, ldg_sgd, lr, beta, per_layer, lambda, center_out, s);
+        if (nt) dispatch_cp<true, float, true>(p, x, ldx, g_sgd, ldg_sgd, lr, beta, per_layer, lambda, center_out, s, e0, e1);
+        else dispatch_cp<true, float, false>(p, x, ldx, g_sgd, ldg_sgd, lr, beta, per_layer, lambda, center_out, s, e0, e1);
     }
     return hipGetLastError();
 }
