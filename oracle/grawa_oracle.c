@@ -16,7 +16,8 @@
  * Sources: vanilla GRAWA weights, Sec. 4.3.1 eq. (2); center and pull, the
  * unnumbered display after eq. (2); MGRAWA, Sec. 5.1 eqs. (3)-(4); LGRAWA,
  * Sec. 5.2 eqs. (5)-(7); local SGD step and its place before the distributed
- * phase, Algorithms 1 and 2; proximity step, same algorithms.
+ * phase, Algorithms 1 and 2; proximity step, same algorithms; running estimate of the
+ * norm scores, Appendix G (Local MGRAWA/LGRAWA algorithm).
  *
  * Every function returns 0 on success, nonzero on a bad argument.
  */
@@ -189,5 +190,37 @@ int oracle_prox(double *xd, int64_t K, int64_t n, const double *c, double mu, do
     for (int64_t m = 0; m < K; ++m)
         for (int64_t i = 0; i < n; ++i)
             xd[m * n + i] = (1.0 - w) * xd[m * n + i] + w * c[i];
+    return 0;
+}
+
+/* Running estimate of the gradient-norm scores, Appendix G (Local MGRAWA/LGRAWA), one local
+ * step for n scores (all workers and layers):
+ *     g_mvg <- gamma g_mvg + (1 - gamma) g_cur
+ *     g_est <- gamma g_mvg / (1 - gamma^t)
+ * t >= 1 is the step counter after its increment.  The second line is kept as printed,
+ * including its leading gamma (a factor common to all workers cancels in the weights);
+ * 0 < gamma < 1 is required (gamma = 0 would make every estimate 0, gamma = 1 divides by 0). */
+int oracle_norm_momentum(double *g_mvg, const double *g_cur, double *g_est, int64_t n,
+                         double gamma, int64_t t)
+{
+    if (!g_mvg || !g_cur || !g_est || n < 0 || t < 1 || !(gamma > 0.0) || !(gamma < 1.0)) return 1;
+    double denom = 1.0 - pow(gamma, (double)t);
+    for (int64_t i = 0; i < n; ++i) {
+        g_mvg[i] = gamma * g_mvg[i] + (1.0 - gamma) * g_cur[i];
+        g_est[i] = gamma * g_mvg[i] / denom;
+    }
+    return 0;
+}
+
+/* Model-level score from per-layer estimates under the MGRAWA policy (eq. (3) applied to the
+ * estimates): A[m] = sum_k est[m][k]. */
+int oracle_sum_layers(const double *est, int64_t K, int64_t L, double *A)
+{
+    if (!est || !A || K < 1 || L < 1) return 1;
+    for (int64_t m = 0; m < K; ++m) {
+        double a = 0.0;
+        for (int64_t k = 0; k < L; ++k) a += est[m * L + k];
+        A[m] = a;
+    }
     return 0;
 }

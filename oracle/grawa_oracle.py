@@ -66,7 +66,9 @@ def _bind(L):
     L.oracle_center.argtypes = [vp, i64, i64, i64, vp, i64, vp, vp]
     L.oracle_pull.argtypes = [vp, i64, i64, vp, dbl]
     L.oracle_prox.argtypes = [vp, i64, i64, vp, dbl, dbl]
-    for name in ("oracle_sumsq", "oracle_layer_norms", "oracle_model_norms", "oracle_weights",
+    L.oracle_norm_momentum.argtypes = [vp, vp, vp, i64, dbl, i64]
+    L.oracle_sum_layers.argtypes = [vp, i64, i64, vp]
+    for name in ("oracle_norm_momentum", "oracle_sum_layers", "oracle_sumsq", "oracle_layer_norms", "oracle_model_norms", "oracle_weights",
                  "oracle_load_params", "oracle_local_sgd", "oracle_center", "oracle_pull",
                  "oracle_prox"):
         getattr(L, name).restype = it
@@ -260,3 +262,75 @@ def lgrawa_update(x, g, off, lam, *, g_sgd=None, lr=0.0, _lib=None):
     A, beta = lgrawa_weights(g, off, _lib=_lib)
     xn, c = center_pull(x, beta, off, lam, g_sgd=g_sgd, lr=lr, _lib=_lib)
     return {"x": xn, "center": c, "beta": beta, "norms": A}
+
+
+# ----------------------------------------------------------------------------
+# Local MGRAWA / LGRAWA (Appendix G): norms from the local optimizer's own gradients
+# ----------------------------------------------------------------------------
+
+class LocalScores:
+    """The running gradient-norm estimate of Appendix G for K workers x L layers:
+    g_mvg (moving average), t (steps since the last communication), g_est."""
+
+    def __init__(self, K, L, gamma, *, _lib=None):
+        self.K, self.L, self.gamma = int(K), int(L), float(gamma)
+        self.g_mvg = np.zeros((self.K, self.L), dtype=np.float64)
+        self.g_est = np.zeros((self.K, self.L), dtype=np.float64)
+        self.t = 0
+        self._lib = _lib
+
+    def step(self, g, off):
+        """One local step: g_cur = per-layer norms of this step's gradients, then the update."""
+        g_cur = layer_norms(grad_sumsq(g, off, _lib=self._lib), _lib=self._lib)
+        self.t += 1
+        _ok((self._lib or lib()).oracle_norm_momentum(_p(self.g_mvg), _p(g_cur), _p(self.g_est),
+                                                      self.K * self.L, self.gamma, self.t), "norm_momentum")
+        return g_cur
+
+    def weights(self, policy):
+        """Weights from the running estimate: 'lgrawa' per layer (eq. (7)), 'mgrawa' from the sum of
+        the layer estimates (eq. (3)-(4))."""
+        if policy == "lgrawa":
+            return weights(self.g_est, _lib=self._lib)
+        if policy == "mgrawa":
+            A = np.empty(self.K, dtype=np.float64)
+            _ok((self._lib or lib()).oracle_sum_layers(_p(self.g_est), self.K, self.L, _p(A)), "sum_layers")
+            return weights(A, _lib=self._lib)
+        raise ValueError(policy)
+
+    def reset(self):
+        """After a communication: g_mvg <- 0, t <- 0."""
+        self.g_mvg[:] = 0.0
+        self.g_est[:] = 0.0
+        self.t = 0
+
+
+def local_grawa_round(x, grads, off, lr, lam, gamma, policy, *, prox_center=None, mu=0.0, tau=1.0, _lib=None):
+    """One round of Appendix G's loop for K workers in lockstep.  For every gradient array in
+    `grads` (one per local step): update the running norm estimate, take the SGD step and, if a
+    stored center is given, the proximity step.  Then form the center from the estimate by the
+    given policy ('lgrawa' or 'mgrawa'), pull, and reset the estimate.
+    Returns dict(x=float64 [K, P], center, beta, g_est)."""
+    Lb = _lib or lib()
+    x = _params(x)
+    off = _offsets(off)
+    K, P = x.shape[0], int(off[-1])
+    sc = LocalScores(K, off.size - 1, gamma, _lib=_lib)
+    xd = np.empty((K, P), dtype=np.float64)
+    _ok(Lb.oracle_load_params(_p(x), K, x.shape[1], 0, P, _p(xd)), "load_params")
+    pc = None if prox_center is None else np.ascontiguousarray(prox_center, dtype=np.float64)
+    for g in grads:
+        sc.step(g, off)
+        garr, gdt = _grads(g)
+        _ok(Lb.oracle_local_sgd(_p(xd), K, P, 0, _p(garr), gdt, garr.shape[1], float(lr)), "local_sgd")
+        if pc is not None:
+            _ok(Lb.oracle_prox(_p(xd), K, P, _p(pc), float(mu), float(tau)), "prox")
+    beta = sc.weights(policy)
+    est = sc.g_est.copy()
+    G = 1 if beta.ndim == 1 else beta.shape[1]
+    b2 = np.ascontiguousarray(beta.reshape(K, G))
+    c = np.empty(P, dtype=np.float64)
+    _ok(Lb.oracle_center(_p(xd), K, P, 0, _p(b2), G, _p(off) if G > 1 else None, _p(c)), "center")
+    _ok(Lb.oracle_pull(_p(xd), K, P, _p(c), float(lam)), "pull")
+    sc.reset()
+    return {"x": xd, "center": c, "beta": beta, "g_est": est}

@@ -41,6 +41,12 @@ MUTANTS = [
     ("bf16_wrong_shift", "<< 16;", "<< 15;"),
     ("prox_swapped", "xd[m * n + i] = (1.0 - w) * xd[m * n + i] + w * c[i];", "xd[m * n + i] = w * xd[m * n + i] + (1.0 - w) * c[i];"),
     ("prox_not_scaled_by_period", "double w = mu / tau;", "double w = mu;"),
+    ("momentum_weights_swapped", "g_mvg[i] = gamma * g_mvg[i] + (1.0 - gamma) * g_cur[i];", "g_mvg[i] = (1.0 - gamma) * g_mvg[i] + gamma * g_cur[i];"),
+    ("momentum_forgets_history", "g_mvg[i] = gamma * g_mvg[i] + (1.0 - gamma) * g_cur[i];", "g_mvg[i] = (1.0 - gamma) * g_cur[i];"),
+    ("bias_correction_missing", "g_est[i] = gamma * g_mvg[i] / denom;", "g_est[i] = gamma * g_mvg[i];"),
+    ("bias_correction_wrong_power", "double denom = 1.0 - pow(gamma, (double)t);", "double denom = 1.0 - pow(gamma, (double)(t + 1));"),
+    ("estimate_without_leading_gamma", "g_est[i] = gamma * g_mvg[i] / denom;", "g_est[i] = g_mvg[i] / denom;"),
+    ("layer_sum_skips_first", "for (int64_t k = 0; k < L; ++k) a += est[m * L + k];", "for (int64_t k = 1; k < L; ++k) a += est[m * L + k];"),
 ]
 
 PIN_TESTS = [(n, f) for n, f in inspect.getmembers(pins, inspect.isfunction) if n.startswith("test_")]

@@ -466,3 +466,96 @@ def test_expected_norm_of_synthetic_gradients():
     g = (s * rng.standard_normal((2, n))).astype(np.float32)
     A = orc.layer_norms(orc.grad_sumsq(g, [0, n]))
     np.testing.assert_allclose(A[:, 0], s * math.sqrt(n), rtol=1e-2)
+
+
+# ----------------------------------------------------------------------------
+# Appendix G: running estimate of the norm scores (Local MGRAWA / LGRAWA)
+# ----------------------------------------------------------------------------
+
+def test_norm_momentum_closed_forms():
+    # constant scores a: g_mvg after t steps is a (1 - gamma^t), so g_est = gamma * a exactly
+    gamma = Fr(9, 10)
+    a = [Fr(3), Fr(1, 2), Fr(7)]
+    sc = orc.LocalScores(1, 3, float(gamma))
+    mv = [Fr(0)] * 3
+    for t in range(1, 8):
+        g_cur = np.array([[float(v) for v in a]])
+        lib = orc.lib()
+        sc.t += 1
+        assert lib.oracle_norm_momentum(orc._p(sc.g_mvg), orc._p(g_cur), orc._p(sc.g_est), 3, float(gamma), sc.t) == 0
+        mv = [gamma * m + (1 - gamma) * v for m, v in zip(mv, a)]                 # the recurrence, exactly
+        assert mv == [v * (1 - gamma ** t) for v in a]                           # its closed form
+        np.testing.assert_allclose(sc.g_mvg[0], as_float(mv), rtol=1e-14)
+        np.testing.assert_allclose(sc.g_est[0], as_float([gamma * v for v in a]), rtol=1e-14)
+    # varying scores: compare with the exact rational recurrence and the printed correction
+    rng = np.random.default_rng(4)
+    gamma = Fr(1, 2)
+    sc = orc.LocalScores(2, 2, float(gamma))
+    mv = [[Fr(0)] * 2 for _ in range(2)]
+    for t in range(1, 6):
+        cur = rng.integers(1, 50, size=(2, 2))
+        g = np.zeros((2, 4), dtype=np.float32)
+        g[:, 0] = cur[:, 0]
+        g[:, 2] = cur[:, 1]                       # one non-zero entry per layer: norm = |entry|
+        got = sc.step(g, [0, 2, 4])
+        np.testing.assert_array_equal(got, cur.astype(np.float64))
+        mv = [[gamma * mv[m][l] + (1 - gamma) * int(cur[m, l]) for l in range(2)] for m in range(2)]
+        est = [[gamma * mv[m][l] / (1 - gamma ** t) for l in range(2)] for m in range(2)]
+        np.testing.assert_allclose(sc.g_mvg, np.array([as_float(r) for r in mv]), rtol=1e-15)
+        np.testing.assert_allclose(sc.g_est, np.array([as_float(r) for r in est]), rtol=1e-15)
+    assert sc.t == 5
+    # the leading gamma is common to all workers: weights equal those of the plain bias-corrected average
+    plain = np.array([as_float([mv[m][l] / (1 - gamma ** 5) for l in range(2)]) for m in range(2)])
+    np.testing.assert_allclose(sc.weights("lgrawa"), orc.weights(plain), rtol=1e-14)
+    np.testing.assert_allclose(sc.weights("mgrawa"), orc.weights(plain.sum(axis=1)), rtol=1e-14)
+    sc.reset()
+    assert sc.t == 0 and not sc.g_mvg.any()
+    # gamma outside (0, 1) is rejected
+    for bad in (0.0, 1.0, -0.1, 1.5):
+        z = np.zeros(1)
+        assert orc.lib().oracle_norm_momentum(orc._p(z), orc._p(z), orc._p(z), 1, bad, 1) != 0
+
+
+def test_local_grawa_round_single_step_equals_fused_update():
+    # one local step with the same gradient: the estimate is gamma * (1-gamma)/(1-gamma) * norm = gamma * norm,
+    # a common factor, so the round equals the fused SGD + LGRAWA / MGRAWA update of the main algorithms
+    off, x, g = _random_problem(123, K=4)
+    lr, lam = 0.1, 0.3
+    r = orc.local_grawa_round(x, [g], off, lr, lam, 0.7, "lgrawa")
+    f = orc.lgrawa_update(x, g, off, lam, g_sgd=g, lr=lr)
+    np.testing.assert_allclose(r["beta"], f["beta"], rtol=1e-13)
+    np.testing.assert_allclose(r["x"], f["x"], rtol=1e-12, atol=1e-16)
+    r = orc.local_grawa_round(x, [g], off, lr, lam, 0.7, "mgrawa")
+    f = orc.mgrawa_update(x, g, off, lam, "layersum", g_sgd=g, lr=lr)
+    np.testing.assert_allclose(r["beta"], f["beta"], rtol=1e-13)
+    np.testing.assert_allclose(r["x"], f["x"], rtol=1e-12, atol=1e-16)
+
+
+def test_local_grawa_round_several_steps():
+    off, x, g0 = _random_problem(124, K=3)
+    _, _, g1 = _random_problem(125, K=3)
+    _, _, g2 = _random_problem(126, K=3, bf16=True)
+    P = int(off[-1])
+    lr, lam, gamma, mu, tau = 0.05, 0.4, 0.9, 0.05, 16.0
+    rng = np.random.default_rng(2)
+    cprev = 0.05 * rng.standard_normal(P)
+    r = orc.local_grawa_round(x, [g0, g1, g2], off, lr, lam, gamma, "lgrawa", prox_center=cprev, mu=mu, tau=tau)
+    # independent numpy statement of the same loop
+    from parity_util import grads_to_f64
+    cur = x[:, :P].astype(np.float64)
+    mvg = np.zeros((3, off.size - 1))
+    w = mu / tau
+    for t, g in enumerate((g0, g1, g2), start=1):
+        gd = grads_to_f64(g)[:, :P]
+        norms = np.array([[np.linalg.norm(gd[m, off[l]:off[l + 1]]) for l in range(off.size - 1)] for m in range(3)])
+        mvg = gamma * mvg + (1 - gamma) * norms
+        est = gamma * mvg / (1 - gamma ** t)
+        cur = cur - lr * gd
+        cur = (1 - w) * cur + w * cprev
+    beta = (1 / est) / (1 / est).sum(axis=0)
+    layer_of = np.repeat(np.arange(off.size - 1), np.diff(off))
+    c = (beta[:, layer_of] * cur).sum(axis=0)
+    want = (1 - lam) * cur + lam * c
+    np.testing.assert_allclose(r["g_est"], est, rtol=1e-13)
+    np.testing.assert_allclose(r["beta"], beta, rtol=1e-13)
+    np.testing.assert_allclose(r["x"], want, rtol=1e-11, atol=1e-15)
