@@ -157,6 +157,55 @@ grawa_status_t grawa_lgrawa_update_sgd(grawa_plan_t *plan, float *x, int64_t ldx
                                        float *center_out, float *weights_out, void *stream);
 
 /*
+ * Local SGD step followed by the proximity step of Algorithms 1 and 2 (the line
+ * marked "Prox."), for every worker:
+ *   x_k <- x_k - lr * g_k ;   x_k <- (1 - mu/tau) x_k + (mu/tau) x_C
+ * center: device float [P], the center stored by the last distributed phase
+ * (the center_out of an update call); it is read once per column for all K
+ * workers.  mu is the proximity strength, tau the communication period;
+ * 0 <= mu <= tau, tau > 0.  Needs no plan.  K <= 64 (UNSUPPORTED beyond).
+ */
+grawa_status_t grawa_local_sgd_prox(float *x, int64_t ldx, const void *g, int64_t ldg,
+                                    grawa_dtype_t g_dtype, int K, int64_t P, float lr,
+                                    const float *center, float mu, float tau, void *stream);
+
+/*
+ * Local MGRAWA / LGRAWA (Appendix G): the gradient-norm scores come from the local
+ * optimizer's own gradients instead of a separate accumulation phase.
+ *
+ * grawa_local_step_scored: one local step of all K workers, in the order of the
+ * appendix's algorithm, with the gradient read ONCE:
+ *   g_cur[k][l] = ||g_k restricted to layer l||_F
+ *   t <- t + 1 ;  g_mvg <- gamma g_mvg + (1 - gamma) g_cur          (kept in the plan, fp64)
+ *   x_k <- x_k - lr g_k ;  if center != NULL: x_k <- (1 - mu/tau) x_k + (mu/tau) center
+ * 0 < gamma < 1, and gamma must not change between two communications
+ * (INVALID_ARG).  K <= 64.
+ *
+ * grawa_local_lgrawa_update / grawa_local_mgrawa_update: the communication step:
+ *   g_est = gamma g_mvg / (1 - gamma^t)            (as printed, leading gamma included)
+ *   weights from g_est: per layer (eq. (7)), or per model from the sum of a
+ *   worker's layer estimates (eq. (3)-(4)); center and pull as in the calls above;
+ *   then g_mvg <- 0, t <- 0.
+ * est_out (device float [K][L] or NULL) receives g_est, weights_out the weights
+ * ([K][L] or [K]).  INVALID_ARG if no local step was taken since the last
+ * communication.  The step counter t lives in the plan on the host: all calls on
+ * one plan must come from one thread, in stream order.
+ *
+ * grawa_local_scores_reset: g_mvg <- 0, t <- 0 without a communication.
+ */
+grawa_status_t grawa_local_step_scored(grawa_plan_t *plan, float *x, int64_t ldx, const void *g,
+                                       int64_t ldg, grawa_dtype_t g_dtype, float lr,
+                                       const float *center, float mu, float tau, float gamma,
+                                       void *stream);
+grawa_status_t grawa_local_lgrawa_update(grawa_plan_t *plan, float *x, int64_t ldx, float lambda,
+                                         float *center_out, float *weights_out, float *est_out,
+                                         void *stream);
+grawa_status_t grawa_local_mgrawa_update(grawa_plan_t *plan, float *x, int64_t ldx, float lambda,
+                                         float *center_out, float *weights_out, float *est_out,
+                                         void *stream);
+grawa_status_t grawa_local_scores_reset(grawa_plan_t *plan, void *stream);
+
+/*
  * Measurement aids (not part of the method).
  *
  * grawa_plan_profile: with enable != 0 the plan attaches a start and a stop

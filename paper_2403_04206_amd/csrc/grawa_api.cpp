@@ -115,7 +115,7 @@ grawa_status_t run_update(grawa_plan *p, float *x, int64_t ldx, const void *g, i
 
     GRAWA_TRY_HIP(grawa_launch_sumsq(p, g, ldg, dt, s, prof ? ev[0] : nullptr, prof ? ev[1] : nullptr));
 
-    GRAWA_TRY_HIP(grawa_launch_finalize_layers(p, nullptr, per_layer ? weights_out : nullptr, s));
+    GRAWA_TRY_HIP(grawa_launch_finalize_layers(p, nullptr, per_layer ? weights_out : nullptr, s, 0, 0.0));
     if (!per_layer) GRAWA_TRY_HIP(grawa_launch_finalize_model(p, mode, weights_out, s));
 
     GRAWA_TRY_HIP(grawa_launch_center_pull(p, x, ldx, per_layer ? p->d_beta_layer : p->d_beta_model,
@@ -222,7 +222,8 @@ grawa_status_t grawa_plan_create(grawa_plan_t **out, int K, int64_t P, int L,
     const size_t b_A = round256(sizeof(float) * (size_t)K * (size_t)L);
     const size_t b_bl = b_A;
     const size_t b_bm = round256(sizeof(float) * (size_t)K);
-    p->ws_bytes = b_off + b_cells + b_tiles + b_lt0 + b_part + b_S + b_A + b_bl + b_bm;
+    const size_t b_mvg = b_S;
+    p->ws_bytes = b_off + b_cells + b_tiles + b_lt0 + b_part + b_S + b_A + b_bl + b_bm + b_mvg;
     if (hipMalloc(&p->ws, p->ws_bytes) != hipSuccess) {
         (void)hipGetLastError();
         delete p;
@@ -237,13 +238,14 @@ grawa_status_t grawa_plan_create(grawa_plan_t **out, int K, int64_t P, int L,
     p->d_S = reinterpret_cast<double *>(w); w += b_S;
     p->d_A = reinterpret_cast<float *>(w); w += b_A;
     p->d_beta_layer = reinterpret_cast<float *>(w); w += b_bl;
-    p->d_beta_model = reinterpret_cast<float *>(w);
+    p->d_beta_model = reinterpret_cast<float *>(w); w += b_bm;
+    p->d_mvg = reinterpret_cast<double *>(w);
 
     if (hipMemcpy(p->d_off, off.data(), sizeof(int64_t) * ((size_t)L + 1), hipMemcpyHostToDevice) != hipSuccess ||
         hipMemcpy(p->d_cell_layer, cell_layer.data(), sizeof(int32_t) * (size_t)nc, hipMemcpyHostToDevice) != hipSuccess ||
         hipMemcpy(p->d_tiles, tiles.data(), sizeof(GrawaTile) * (size_t)nt, hipMemcpyHostToDevice) != hipSuccess ||
         hipMemcpy(p->d_layer_tile0, layer_tile0.data(), sizeof(int32_t) * ((size_t)L + 1), hipMemcpyHostToDevice) != hipSuccess ||
-        hipMemset(p->d_partials, 0, b_part + b_S + b_A + b_bl + b_bm) != hipSuccess) {
+        hipMemset(p->d_partials, 0, b_part + b_S + b_A + b_bl + b_bm + b_mvg) != hipSuccess) {
         (void)hipFree(p->ws);
         delete p;
         return GRAWA_ERR_HIP;
@@ -284,7 +286,7 @@ grawa_status_t grawa_grad_norms(grawa_plan_t *p, const void *g, int64_t ldg, gra
     if (!guard.ok) return GRAWA_ERR_HIP;
     hipStream_t s = static_cast<hipStream_t>(stream);
     GRAWA_TRY_HIP(grawa_launch_sumsq(p, g, ldg, dt, s, nullptr, nullptr));
-    GRAWA_TRY_HIP(grawa_launch_finalize_layers(p, norms_out, nullptr, s));
+    GRAWA_TRY_HIP(grawa_launch_finalize_layers(p, norms_out, nullptr, s, 0, 0.0));
     return GRAWA_OK;
 }
 
@@ -353,6 +355,102 @@ grawa_status_t grawa_local_sgd(float *x, int64_t ldx, const void *g, int64_t ldg
     if (st != GRAWA_OK) return st;
     if (!std::isfinite(lr)) return GRAWA_ERR_INVALID_ARG;
     GRAWA_TRY_HIP(grawa_launch_local_sgd(x, ldx, g, ldg, dt, K, P, lr, static_cast<hipStream_t>(stream)));
+    return GRAWA_OK;
+}
+
+grawa_status_t grawa_local_sgd_prox(float *x, int64_t ldx, const void *g, int64_t ldg, grawa_dtype_t dt, int K,
+                                    int64_t P, float lr, const float *center, float mu, float tau, void *stream)
+{
+    if (!x || !center || K < 1 || P < 1 || ldx < P) return GRAWA_ERR_INVALID_ARG;
+    if (K > 64 || P >= ((int64_t)1 << 36)) return GRAWA_ERR_UNSUPPORTED;
+    if (!aligned16(x) || (ldx % 4) != 0 || !aligned16(center)) return GRAWA_ERR_ALIGNMENT;
+    grawa_status_t st = check_grads(P, g, ldg, dt);
+    if (st != GRAWA_OK) return st;
+    if (!std::isfinite(lr) || !std::isfinite(mu) || !std::isfinite(tau) || !(tau > 0.f) || mu < 0.f || mu > tau)
+        return GRAWA_ERR_INVALID_ARG;
+    const int T = 4096;
+    const int64_t nt = (P + T - 1) / T;
+    GRAWA_TRY_HIP(grawa_launch_rows_step(x, ldx, g, ldg, dt, lr, center, mu / tau, nullptr, T, nt, K, P, nullptr,
+                                         static_cast<hipStream_t>(stream)));
+    return GRAWA_OK;
+}
+
+grawa_status_t grawa_local_step_scored(grawa_plan_t *p, float *x, int64_t ldx, const void *g, int64_t ldg,
+                                       grawa_dtype_t dt, float lr, const float *center, float mu, float tau,
+                                       float gamma, void *stream)
+{
+    grawa_status_t st;
+    if ((st = check_params(p, x, ldx)) != GRAWA_OK) return st;
+    if ((st = check_grads(p->P, g, ldg, dt)) != GRAWA_OK) return st;
+    if (p->K > 64) return GRAWA_ERR_UNSUPPORTED;
+    if (!std::isfinite(lr) || !(gamma > 0.f) || !(gamma < 1.f)) return GRAWA_ERR_INVALID_ARG;
+    if (p->local_t > 0 && (double)gamma != p->local_gamma) return GRAWA_ERR_INVALID_ARG; /* one gamma per round */
+    float w = 0.f;
+    if (center) {
+        if (!aligned16(center)) return GRAWA_ERR_ALIGNMENT;
+        if (!std::isfinite(mu) || !std::isfinite(tau) || !(tau > 0.f) || mu < 0.f || mu > tau)
+            return GRAWA_ERR_INVALID_ARG;
+        w = mu / tau;
+    }
+    DeviceGuard guard(p->device);
+    if (!guard.ok) return GRAWA_ERR_HIP;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    GRAWA_TRY_HIP(grawa_launch_rows_step(x, ldx, g, ldg, dt, lr, center, w, p->d_tiles, p->tile_elems, p->n_tiles,
+                                         p->K, p->P, p->d_partials, s));
+    GRAWA_TRY_HIP(grawa_launch_finalize_layers(p, nullptr, nullptr, s, 1, (double)gamma));
+    p->local_t += 1;
+    p->local_gamma = (double)gamma;
+    return GRAWA_OK;
+}
+
+namespace {
+grawa_status_t local_update(grawa_plan_t *p, float *x, int64_t ldx, int per_layer, float lambda, float *center_out,
+                            float *weights_out, float *est_out, hipStream_t s)
+{
+    grawa_status_t st;
+    if ((st = check_params(p, x, ldx)) != GRAWA_OK) return st;
+    if ((st = check_lambda(lambda)) != GRAWA_OK) return st;
+    if ((st = check_center(center_out)) != GRAWA_OK) return st;
+    if (p->local_t < 1) return GRAWA_ERR_INVALID_ARG; /* no local step since the last communication */
+    DeviceGuard guard(p->device);
+    if (!guard.ok) return GRAWA_ERR_HIP;
+    const double scale = p->local_gamma / (1.0 - std::pow(p->local_gamma, (double)p->local_t));
+    GRAWA_TRY_HIP(grawa_launch_local_weights(p, scale, per_layer, weights_out, est_out, s));
+    const bool prof = prof_active(p);
+    hipEvent_t *ev = prof ? p->ev + 4 * (size_t)p->profile_n : nullptr;
+    GRAWA_TRY_HIP(grawa_launch_center_pull(p, x, ldx, per_layer ? p->d_beta_layer : p->d_beta_model, per_layer,
+                                           lambda, nullptr, 0, GRAWA_F32, 0.f, 0, center_out, s,
+                                           prof ? ev[2] : nullptr, prof ? ev[3] : nullptr));
+    if (prof) {
+        p->profile_pull_only = 1;
+        p->profile_n += 1;
+    }
+    GRAWA_TRY_HIP(grawa_launch_zero_estimate(p, s));
+    p->local_t = 0;
+    return GRAWA_OK;
+}
+} // namespace
+
+grawa_status_t grawa_local_lgrawa_update(grawa_plan_t *p, float *x, int64_t ldx, float lambda, float *center_out,
+                                         float *weights_out, float *est_out, void *stream)
+{
+    return local_update(p, x, ldx, 1, lambda, center_out, weights_out, est_out, static_cast<hipStream_t>(stream));
+}
+
+grawa_status_t grawa_local_mgrawa_update(grawa_plan_t *p, float *x, int64_t ldx, float lambda, float *center_out,
+                                         float *weights_out, float *est_out, void *stream)
+{
+    return local_update(p, x, ldx, 0, lambda, center_out, weights_out, est_out, static_cast<hipStream_t>(stream));
+}
+
+grawa_status_t grawa_local_scores_reset(grawa_plan_t *p, void *stream)
+{
+    if (!p) return GRAWA_ERR_INVALID_ARG;
+    DeviceGuard guard(p->device);
+    if (!guard.ok) return GRAWA_ERR_HIP;
+    GRAWA_TRY_HIP(grawa_launch_zero_estimate(p, static_cast<hipStream_t>(stream)));
+    p->local_t = 0;
+    p->local_gamma = 0.0;
     return GRAWA_OK;
 }
 

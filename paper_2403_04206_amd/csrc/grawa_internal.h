@@ -38,6 +38,9 @@ struct grawa_plan {
     float *d_A;             // [K][L] layer norms
     float *d_beta_layer;    // [K][L] per-layer weights
     float *d_beta_model;    // [K] model-level weights
+    double *d_mvg;          // [K][L] moving average of the layer norms (running estimate, Appendix G)
+    int64_t local_t;        // local steps since the last communication
+    double local_gamma;     // momentum of the running estimate used so far (0 = none yet)
     // measurement aid
     int profile_on;
     int profile_n;
@@ -50,7 +53,13 @@ struct grawa_plan {
 hipError_t grawa_launch_sumsq(const grawa_plan *p, const void *g, int64_t ldg, grawa_dtype_t dt,
                               hipStream_t s, hipEvent_t e0, hipEvent_t e1);
 hipError_t grawa_launch_finalize_layers(const grawa_plan *p, float *norms_user, float *beta_user,
-                                        hipStream_t s);
+                                        hipStream_t s, int update_estimate, double gamma);
+hipError_t grawa_launch_local_weights(const grawa_plan *p, double scale, int per_layer, float *beta_user,
+                                      float *est_user, hipStream_t s);
+hipError_t grawa_launch_zero_estimate(const grawa_plan *p, hipStream_t s);
+hipError_t grawa_launch_rows_step(float *x, int64_t ldx, const void *g, int64_t ldg, grawa_dtype_t dt, float lr,
+                                  const float *center, float w, const GrawaTile *tiles, int tile_elems,
+                                  int64_t n_tiles, int K, int64_t P, double *partials, hipStream_t s);
 hipError_t grawa_launch_finalize_model(const grawa_plan *p, grawa_norm_mode_t mode, float *beta_user,
                                        hipStream_t s);
 hipError_t grawa_launch_center_pull(const grawa_plan *p, float *x, int64_t ldx, const float *beta,

@@ -298,7 +298,7 @@ __device__ __forceinline__ double wave_strided_sum(const double *__restrict__ p,
 __global__ __launch_bounds__(GRAWA_FIN_BLOCK) void k_finalize_layers(
     const double *__restrict__ partials, int64_t n_tiles, const int32_t *__restrict__ layer_tile0,
     int K, int L, double *__restrict__ S, float *__restrict__ A, float *__restrict__ A_user,
-    float *__restrict__ beta, float *__restrict__ beta_user)
+    float *__restrict__ beta, float *__restrict__ beta_user, double *__restrict__ mvg, double gamma)
 {
     __shared__ double sA[GRAWA_MAX_WORKERS];
     __shared__ double sw[GRAWA_FIN_WAVES];
@@ -336,9 +336,55 @@ __global__ __launch_bounds__(GRAWA_FIN_BLOCK) void k_finalize_layers(
         A[(int64_t)k * L + l] = (float)a;
         if (A_user) A_user[(int64_t)k * L + l] = (float)a;
         sA[k] = a;
+        // running estimate of Appendix G: g_mvg <- gamma g_mvg + (1 - gamma) g_cur
+        if (mvg) mvg[(int64_t)k * L + l] = gamma * mvg[(int64_t)k * L + l] + (1.0 - gamma) * a;
     }
     __syncthreads();
     if (wave == 0) group_weights(sA, K, beta + l, L, beta_user ? beta_user + l : nullptr);
+}
+
+// Weights from the running norm estimate g_est = scale * g_mvg (Appendix G; scale =
+// gamma / (1 - gamma^t)).  per_layer: grid L, block l normalises column l over the workers
+// (eq. (7)); otherwise grid 1: score of worker k is the sum of its layer estimates (eq. (3)
+// applied to the estimates), then eq. (4).  est_user (float [K][L], may be null) receives g_est.
+__global__ __launch_bounds__(GRAWA_FIN_BLOCK) void k_local_weights(const double *__restrict__ mvg, double scale,
+                                                                   int K, int L, int per_layer,
+                                                                   float *__restrict__ beta,
+                                                                   float *__restrict__ beta_user,
+                                                                   float *__restrict__ est_user)
+{
+    __shared__ double sA[GRAWA_MAX_WORKERS];
+    const int lane = threadIdx.x & (GRAWA_WAVE - 1);
+    const int wave = threadIdx.x / GRAWA_WAVE;
+    if (per_layer) {
+        const int l = blockIdx.x;
+        for (int k = threadIdx.x; k < K; k += GRAWA_FIN_BLOCK) {
+            const double e = scale * mvg[(int64_t)k * L + l];
+            sA[k] = e;
+            if (est_user) est_user[(int64_t)k * L + l] = (float)e;
+        }
+        __syncthreads();
+        if (wave == 0) group_weights(sA, K, beta + l, L, beta_user ? beta_user + l : nullptr);
+    } else {
+        for (int k = wave; k < K; k += GRAWA_FIN_WAVES) {
+            double s = 0.0;
+            for (int l = lane; l < L; l += GRAWA_WAVE) {
+                const double e = scale * mvg[(int64_t)k * L + l];
+                s += e;
+                if (est_user) est_user[(int64_t)k * L + l] = (float)e;
+            }
+            s = wave_sum(s);
+            if (lane == 0) sA[k] = s;
+        }
+        __syncthreads();
+        if (wave == 0) group_weights(sA, K, beta, 1, beta_user);
+    }
+}
+
+__global__ __launch_bounds__(GRAWA_BLOCK) void k_zero_f64(double *__restrict__ p, int64_t n)
+{
+    const int64_t i = (int64_t)blockIdx.x * GRAWA_BLOCK + threadIdx.x;
+    if (i < n) p[i] = 0.0;
 }
 
 // grid 1, block 1024.  Model-level score per worker from the [K][L] squared layer norms:
@@ -481,20 +527,98 @@ __global__ __launch_bounds__(GRAWA_CELL) void k_center_pull_any(
 // local SGD step
 // ---------------------------------------------------------------------------------
 
-// grid (ceil(P/256), K), block 256.  x[k][i] -= lr * g[k][i], one column per lane.
+#define GRAWA_SGD_U 4 // columns per lane of the plain SGD step (8 loads in flight per lane)
+
+// grid (ceil(P/1024), K), block 256.  x[k][i] -= lr * g[k][i]; lane t of block m owns columns
+// 1024 m + t + 256 u, u < 4 (each wave access is one aligned 256-byte piece).
 template <typename GT, bool NT>
 __global__ __launch_bounds__(GRAWA_CELL) void k_local_sgd(float *__restrict__ x, int64_t ldx,
                                                           const GT *__restrict__ g, int64_t ldg,
                                                           int64_t P, float lr)
 {
-    const int64_t cell0 = (int64_t)blockIdx.x * GRAWA_CELL;
+    const int64_t cell0 = (int64_t)blockIdx.x * (GRAWA_CELL * GRAWA_SGD_U);
     const unsigned t = threadIdx.x;
-    if (cell0 + t >= P) return;
     const uint64_t xr = uniform_base(x + (int64_t)blockIdx.y * ldx + cell0);
     const uint64_t gr = uniform_base(g + (int64_t)blockIdx.y * ldg + cell0);
-    const float xv = ld_lane<NT, float>(xr, t * 4u);
-    const float gv = Grad<GT>::template lane<NT>(gr, t * (unsigned)sizeof(GT));
-    st_lane<NT, float>(xr, t * 4u, fmaf(-lr, gv, xv));
+    float xv[GRAWA_SGD_U], gv[GRAWA_SGD_U];
+#pragma unroll
+    for (int u = 0; u < GRAWA_SGD_U; ++u) {
+        const unsigned c = u * GRAWA_CELL + t;
+        xv[u] = gv[u] = 0.f;
+        if (cell0 + c < P) {
+            xv[u] = ld_lane<NT, float>(xr, c * 4u);
+            gv[u] = Grad<GT>::template lane<NT>(gr, c * (unsigned)sizeof(GT));
+        }
+    }
+#pragma unroll
+    for (int u = 0; u < GRAWA_SGD_U; ++u) {
+        const unsigned c = u * GRAWA_CELL + t;
+        if (cell0 + c < P) st_lane<NT, float>(xr, c * 4u, fmaf(-lr, gv[u], xv[u]));
+    }
+}
+
+// Local step of all K workers over one tile of columns (Algorithms 1 and 2; Appendix G):
+//     x_k <- x_k - lr g_k ;   PROX: x_k <- x_k + w (c - x_k), c a stored center, w = mu/tau ;
+//     SCORE: partials[k][tile] = sum over the tile of g_k^2  (for the running norm estimate).
+// grid n_tiles, block 256.  The block walks its tile in aligned chunks of 256 columns; per chunk a
+// lane owns one column and all K rows of it (2K loads in flight, the stored center read once for
+// all K rows), as in the center+pull pass.  tiles == nullptr: uniform tiles of tile_elems columns.
+template <int KT, bool EXACT, typename GT, bool NT, bool PROX, bool SCORE, int WPE>
+__global__ __launch_bounds__(GRAWA_CELL) __attribute__((amdgpu_waves_per_eu(1, WPE))) void k_rows_step(
+    float *__restrict__ x, int64_t ldx, const GT *__restrict__ g, int64_t ldg, float lr,
+    const float *__restrict__ center, float w, const GrawaTile *__restrict__ tiles, int tile_elems,
+    int64_t n_tiles, int K, int64_t P, double *__restrict__ partials)
+{
+    int64_t a, b;
+    if (tiles) {
+        const GrawaTile tl = tiles[blockIdx.x];
+        a = tl.start;
+        b = tl.start + tl.len;
+    } else {
+        a = (int64_t)blockIdx.x * tile_elems;
+        b = a + tile_elems < P ? a + tile_elems : P;
+    }
+    const unsigned t = threadIdx.x;
+    const int nk = EXACT ? KT : K;
+    float acc[KT];
+#pragma unroll
+    for (int k = 0; k < KT; ++k) acc[k] = 0.f;
+
+    for (int64_t c0 = a - (a % GRAWA_CELL); c0 < b; c0 += GRAWA_CELL) { // c0 is wave-uniform
+        const int64_t i = c0 + t;
+        const bool ok = i >= a && i < b;
+        const unsigned xoff = t * 4u, goff = t * (unsigned)sizeof(GT);
+        float v[KT], gv[KT];
+        float cv = 0.f;
+        if (ok) {
+#pragma unroll
+            for (int k = 0; k < KT; ++k)
+                if (k < nk) v[k] = ld_lane<NT, float>(uniform_base(x + (int64_t)k * ldx + c0), xoff);
+#pragma unroll
+            for (int k = 0; k < KT; ++k)
+                if (k < nk) gv[k] = Grad<GT>::template lane<NT>(uniform_base(g + (int64_t)k * ldg + c0), goff);
+            if (PROX) cv = ld_lane<false, float>(uniform_base(center + c0), xoff);
+#pragma unroll
+            for (int k = 0; k < KT; ++k)
+                if (k < nk) {
+                    float r = fmaf(-lr, gv[k], v[k]);
+                    if (PROX) r = fmaf(w, cv - r, r);
+                    if (SCORE) acc[k] = fmaf(gv[k], gv[k], acc[k]);
+                    st_lane<NT, float>(uniform_base(x + (int64_t)k * ldx + c0), xoff, r);
+                }
+        }
+    }
+
+    if (SCORE) {
+        __shared__ double sm[GRAWA_BLOCK / GRAWA_WAVE];
+        for (int k = 0; k < nk; ++k) {
+            float ak = 0.f;
+#pragma unroll
+            for (int kk = 0; kk < KT; ++kk) ak = (kk == k) ? acc[kk] : ak; // keeps acc[] in registers
+            const double tot = block_sum((double)ak, sm);
+            if (t == 0) partials[(int64_t)k * n_tiles + blockIdx.x] = tot;
+        }
+    }
 }
 
 // ---------------------------------------------------------------------------------
@@ -531,11 +655,27 @@ hipError_t grawa_launch_sumsq(const grawa_plan *p, const void *g, int64_t ldg, g
 }
 
 hipError_t grawa_launch_finalize_layers(const grawa_plan *p, float *norms_user, float *beta_user,
-                                        hipStream_t s)
+                                        hipStream_t s, int update_estimate, double gamma)
 {
     k_finalize_layers<<<dim3((unsigned)p->L), dim3(GRAWA_FIN_BLOCK), 0, s>>>(
         p->d_partials, p->n_tiles, p->d_layer_tile0, p->K, p->L, p->d_S, p->d_A, norms_user,
-        p->d_beta_layer, beta_user);
+        p->d_beta_layer, beta_user, update_estimate ? p->d_mvg : nullptr, gamma);
+    return hipGetLastError();
+}
+
+hipError_t grawa_launch_local_weights(const grawa_plan *p, double scale, int per_layer, float *beta_user,
+                                      float *est_user, hipStream_t s)
+{
+    k_local_weights<<<dim3(per_layer ? (unsigned)p->L : 1u), dim3(GRAWA_FIN_BLOCK), 0, s>>>(
+        p->d_mvg, scale, p->K, p->L, per_layer, per_layer ? p->d_beta_layer : p->d_beta_model, beta_user,
+        est_user);
+    return hipGetLastError();
+}
+
+hipError_t grawa_launch_zero_estimate(const grawa_plan *p, hipStream_t s)
+{
+    const int64_t n = (int64_t)p->K * p->L;
+    k_zero_f64<<<dim3((unsigned)((n + GRAWA_BLOCK - 1) / GRAWA_BLOCK)), dim3(GRAWA_BLOCK), 0, s>>>(p->d_mvg, n);
     return hipGetLastError();
 }
 
@@ -631,7 +771,8 @@ hipError_t grawa_launch_center_pull(const grawa_plan *p, float *x, int64_t ldx, 
 hipError_t grawa_launch_local_sgd(float *x, int64_t ldx, const void *g, int64_t ldg, grawa_dtype_t dt,
                                   int K, int64_t P, float lr, hipStream_t s)
 {
-    const int64_t gx = (P + GRAWA_CELL - 1) / GRAWA_CELL;
+    const int64_t per_block = GRAWA_CELL * GRAWA_SGD_U;
+    const int64_t gx = (P + per_block - 1) / per_block;
     const dim3 grid((unsigned)gx, (unsigned)K), block(GRAWA_CELL);
     const bool nt = (int64_t)K * P * 4 > GRAWA_STREAMING_MIN_BYTES && rows_line_aligned(x, ldx, 4) &&
                     rows_line_aligned(g, ldg, dt == GRAWA_BF16 ? 2 : 4);
@@ -642,6 +783,69 @@ hipError_t grawa_launch_local_sgd(float *x, int64_t ldx, const void *g, int64_t 
         if (nt) k_local_sgd<float, true><<<grid, block, 0, s>>>(x, ldx, (const float *)g, ldg, P, lr);
         else k_local_sgd<float, false><<<grid, block, 0, s>>>(x, ldx, (const float *)g, ldg, P, lr);
     }
+    return hipGetLastError();
+}
+
+// K-row local step: SGD (+ proximity step) (+ per-tile sums of squares of the gradient).
+template <int KT, bool EXACT, typename GT, bool NT, bool PROX, bool SCORE>
+static void launch_rows(float *x, int64_t ldx, const void *g, int64_t ldg, float lr, const float *center, float w,
+                        const GrawaTile *tiles, int tile_elems, int64_t n_tiles, int K, int64_t P,
+                        double *partials, hipStream_t s)
+{
+    k_rows_step<KT, EXACT, GT, NT, PROX, SCORE, grawa_waves_for(KT, true)>
+        <<<dim3((unsigned)n_tiles), dim3(GRAWA_CELL), 0, s>>>(x, ldx, (const GT *)g, ldg, lr, center, w, tiles,
+                                                             tile_elems, n_tiles, K, P, partials);
+}
+
+template <typename GT, bool NT, bool PROX, bool SCORE>
+static bool dispatch_rows(float *x, int64_t ldx, const void *g, int64_t ldg, float lr, const float *center, float w,
+                          const GrawaTile *tiles, int tile_elems, int64_t n_tiles, int K, int64_t P,
+                          double *partials, hipStream_t s)
+{
+#define GRAWA_ROWS_CASE(N) \
+    case N: launch_rows<N, true, GT, NT, PROX, SCORE>(x, ldx, g, ldg, lr, center, w, tiles, tile_elems, n_tiles, K, P, partials, s); break;
+    switch (K) {
+        GRAWA_ROWS_CASE(1) GRAWA_ROWS_CASE(2) GRAWA_ROWS_CASE(3) GRAWA_ROWS_CASE(4) GRAWA_ROWS_CASE(5) GRAWA_ROWS_CASE(6)
+        GRAWA_ROWS_CASE(7) GRAWA_ROWS_CASE(8) GRAWA_ROWS_CASE(9) GRAWA_ROWS_CASE(10) GRAWA_ROWS_CASE(11) GRAWA_ROWS_CASE(12)
+        GRAWA_ROWS_CASE(13) GRAWA_ROWS_CASE(14) GRAWA_ROWS_CASE(15) GRAWA_ROWS_CASE(16) GRAWA_ROWS_CASE(24)
+        GRAWA_ROWS_CASE(32)
+    default:
+        if (K > 64) return false;
+        if (K <= 32) launch_rows<32, false, GT, NT, PROX, SCORE>(x, ldx, g, ldg, lr, center, w, tiles, tile_elems, n_tiles, K, P, partials, s);
+        else launch_rows<64, false, GT, NT, PROX, SCORE>(x, ldx, g, ldg, lr, center, w, tiles, tile_elems, n_tiles, K, P, partials, s);
+    }
+#undef GRAWA_ROWS_CASE
+    return true;
+}
+
+// Returns hipErrorInvalidValue when K exceeds what the kernel family covers (K > 64).
+hipError_t grawa_launch_rows_step(float *x, int64_t ldx, const void *g, int64_t ldg, grawa_dtype_t dt, float lr,
+                                  const float *center, float w, const GrawaTile *tiles, int tile_elems,
+                                  int64_t n_tiles, int K, int64_t P, double *partials, hipStream_t s)
+{
+    const bool nt = (int64_t)K * P * 4 > GRAWA_STREAMING_MIN_BYTES && rows_line_aligned(x, ldx, 4) &&
+                    rows_line_aligned(g, ldg, dt == GRAWA_BF16 ? 2 : 4);
+    const bool prox = center != nullptr, score = partials != nullptr;
+    bool ok;
+#define GRAWA_ROWS_GO(GT, NT, PROX, SCORE) \
+    ok = dispatch_rows<GT, NT, PROX, SCORE>(x, ldx, g, ldg, lr, center, w, tiles, tile_elems, n_tiles, K, P, partials, s)
+#define GRAWA_ROWS_PS(GT, NT)                         \
+    do {                                              \
+        if (prox && score) GRAWA_ROWS_GO(GT, NT, true, true);   \
+        else if (prox) GRAWA_ROWS_GO(GT, NT, true, false);      \
+        else if (score) GRAWA_ROWS_GO(GT, NT, false, true);     \
+        else GRAWA_ROWS_GO(GT, NT, false, false);               \
+    } while (0)
+    if (dt == GRAWA_BF16) {
+        if (nt) GRAWA_ROWS_PS(uint16_t, true);
+        else GRAWA_ROWS_PS(uint16_t, false);
+    } else {
+        if (nt) GRAWA_ROWS_PS(float, true);
+        else GRAWA_ROWS_PS(float, false);
+    }
+#undef GRAWA_ROWS_PS
+#undef GRAWA_ROWS_GO
+    if (!ok) return hipErrorInvalidValue;
     return hipGetLastError();
 }
 

@@ -56,6 +56,11 @@ def lib():
         "grawa_local_sgd": (it, [vp, i64, vp, i64, it, it, i64, fl, vp]),
         "grawa_mgrawa_update_sgd": (it, [vp, vp, i64, vp, i64, it, it, fl, vp, i64, fl, vp, vp, vp]),
         "grawa_lgrawa_update_sgd": (it, [vp, vp, i64, vp, i64, it, fl, vp, i64, fl, vp, vp, vp]),
+        "grawa_local_sgd_prox": (it, [vp, i64, vp, i64, it, it, i64, fl, vp, fl, fl, vp]),
+        "grawa_local_step_scored": (it, [vp, vp, i64, vp, i64, it, fl, vp, fl, fl, fl, vp]),
+        "grawa_local_lgrawa_update": (it, [vp, vp, i64, fl, vp, vp, vp, vp]),
+        "grawa_local_mgrawa_update": (it, [vp, vp, i64, fl, vp, vp, vp, vp]),
+        "grawa_local_scores_reset": (it, [vp, vp]),
         "grawa_plan_profile": (it, [vp, it]),
         "grawa_plan_profile_read": (it, [vp, C.POINTER(it), C.POINTER(dbl), C.POINTER(dbl)]),
         "grawa_stream_copy": (it, [vp, vp, i64, vp]),
@@ -197,6 +202,26 @@ class Plan:
         _check(lib().grawa_center_pull(self._h, xp, ldx, _ptr(weights), per_layer, float(lam), _ptr(center_out),
                                        _stream(stream)), "grawa_center_pull")
 
+    # -- Local MGRAWA / LGRAWA (Appendix G) -----------------------------------------
+    def local_step_scored(self, x, g, lr, gamma, center=None, mu=0.0, tau=1.0, stream=None):
+        xp, ldx = _params(x)
+        gp, ldg, dt = _grads(g)
+        _check(lib().grawa_local_step_scored(self._h, xp, ldx, gp, ldg, dt, float(lr), _ptr(center), float(mu),
+                                             float(tau), float(gamma), _stream(stream)), "grawa_local_step_scored")
+
+    def local_lgrawa_update(self, x, lam, center_out=None, weights_out=None, est_out=None, stream=None):
+        xp, ldx = _params(x)
+        _check(lib().grawa_local_lgrawa_update(self._h, xp, ldx, float(lam), _ptr(center_out), _ptr(weights_out),
+                                               _ptr(est_out), _stream(stream)), "grawa_local_lgrawa_update")
+
+    def local_mgrawa_update(self, x, lam, center_out=None, weights_out=None, est_out=None, stream=None):
+        xp, ldx = _params(x)
+        _check(lib().grawa_local_mgrawa_update(self._h, xp, ldx, float(lam), _ptr(center_out), _ptr(weights_out),
+                                               _ptr(est_out), _stream(stream)), "grawa_local_mgrawa_update")
+
+    def local_scores_reset(self, stream=None):
+        _check(lib().grawa_local_scores_reset(self._h, _stream(stream)), "grawa_local_scores_reset")
+
     # -- measurement aid ------------------------------------------------------------
     def profile(self, enable: bool):
         _check(lib().grawa_plan_profile(self._h, 1 if enable else 0), "grawa_plan_profile")
@@ -214,6 +239,16 @@ def local_sgd(x, g, lr, P=None, stream=None):
     K = x.shape[0]
     P = x.shape[1] if P is None else int(P)
     _check(lib().grawa_local_sgd(xp, ldx, gp, ldg, dt, K, P, float(lr), _stream(stream)), "grawa_local_sgd")
+
+
+def local_sgd_prox(x, g, lr, center, mu, tau, P=None, stream=None):
+    """grawa_local_sgd_prox: SGD step then the proximity step toward the stored center."""
+    xp, ldx = _params(x)
+    gp, ldg, dt = _grads(g)
+    K = x.shape[0]
+    P = x.shape[1] if P is None else int(P)
+    _check(lib().grawa_local_sgd_prox(xp, ldx, gp, ldg, dt, K, P, float(lr), _ptr(center), float(mu), float(tau),
+                                      _stream(stream)), "grawa_local_sgd_prox")
 
 
 def stream_copy(dst, src, stream=None):
