@@ -162,27 +162,34 @@ grawa_status_t grawa_plan_create(grawa_plan_t **out, int K, int64_t P, int L,
     for (int l = 0; l < L; ++l)
         if (off[(size_t)l + 1] <= off[(size_t)l]) return GRAWA_ERR_INVALID_ARG;
 
-    // Tile map: cut every layer at the multiples of T of the flat index, so tile starts are
-    // either a multiple of T or a layer start and no tile crosses a layer boundary.
+    // Tile maps: cut every layer at the multiples of T of the flat index, so tile starts are
+    // either a multiple of T or a layer start and no tile crosses a layer boundary.  One map for
+    // the norm pass (long tiles), one for the scored local step (1024-column tiles).
     const int T = tile_elems_for(K, P);
-    std::vector<GrawaTile> tiles;
-    std::vector<int32_t> layer_tile0((size_t)L + 1);
+    const int TR = 1024;
     const int64_t max_tiles = (int64_t)1 << 24; // keeps grid.x * 256 below 2^32
-    if (P / T + L > max_tiles) return GRAWA_ERR_UNSUPPORTED;
-    tiles.reserve((size_t)(P / T + L + 1));
-    for (int l = 0; l < L; ++l) {
-        layer_tile0[(size_t)l] = (int32_t)tiles.size();
-        int64_t s = off[(size_t)l];
-        const int64_t e = off[(size_t)l + 1];
-        while (s < e) {
-            int64_t stop = (s / T + 1) * T;
-            if (stop > e) stop = e;
-            tiles.push_back(GrawaTile{s, (int32_t)(stop - s), (int32_t)l});
-            s = stop;
+    if (P / T + L > max_tiles || P / TR + L > max_tiles) return GRAWA_ERR_UNSUPPORTED;
+    std::vector<GrawaTile> tiles, rtiles;
+    std::vector<int32_t> layer_tile0((size_t)L + 1), layer_rtile0((size_t)L + 1);
+    auto cut = [&](int len, std::vector<GrawaTile> &out, std::vector<int32_t> &first) {
+        out.reserve((size_t)(P / len + L + 1));
+        for (int l = 0; l < L; ++l) {
+            first[(size_t)l] = (int32_t)out.size();
+            int64_t s = off[(size_t)l];
+            const int64_t e = off[(size_t)l + 1];
+            while (s < e) {
+                int64_t stop = (s / len + 1) * len;
+                if (stop > e) stop = e;
+                out.push_back(GrawaTile{s, (int32_t)(stop - s), (int32_t)l});
+                s = stop;
+            }
         }
-    }
-    layer_tile0[(size_t)L] = (int32_t)tiles.size();
+        first[(size_t)L] = (int32_t)out.size();
+    };
+    cut(T, tiles, layer_tile0);
+    cut(TR, rtiles, layer_rtile0);
     const int64_t nt = (int64_t)tiles.size();
+    const int64_t nrt = (int64_t)rtiles.size();
 
     // Cell map of the center+pull pass: block m covers columns [256 m, 256 m + 256).
     const int64_t cell = 256;
@@ -207,6 +214,7 @@ grawa_status_t grawa_plan_create(grawa_plan_t **out, int K, int64_t P, int L,
     p->P = P;
     p->tile_elems = T;
     p->n_tiles = nt;
+    p->n_rtiles = nrt;
     p->n_cells = nc;
     if (hipGetDevice(&p->device) != hipSuccess) {
         delete p;
@@ -216,14 +224,15 @@ grawa_status_t grawa_plan_create(grawa_plan_t **out, int K, int64_t P, int L,
     const size_t b_off = round256(sizeof(int64_t) * ((size_t)L + 1));
     const size_t b_cells = round256(sizeof(int32_t) * (size_t)nc);
     const size_t b_tiles = round256(sizeof(GrawaTile) * (size_t)nt);
+    const size_t b_rtiles = round256(sizeof(GrawaTile) * (size_t)nrt);
     const size_t b_lt0 = round256(sizeof(int32_t) * ((size_t)L + 1));
-    const size_t b_part = round256(sizeof(double) * (size_t)K * (size_t)nt);
+    const size_t b_part = round256(sizeof(double) * (size_t)K * (size_t)(nrt > nt ? nrt : nt));
     const size_t b_S = round256(sizeof(double) * (size_t)K * (size_t)L);
     const size_t b_A = round256(sizeof(float) * (size_t)K * (size_t)L);
     const size_t b_bl = b_A;
     const size_t b_bm = round256(sizeof(float) * (size_t)K);
     const size_t b_mvg = b_S;
-    p->ws_bytes = b_off + b_cells + b_tiles + b_lt0 + b_part + b_S + b_A + b_bl + b_bm + b_mvg;
+    p->ws_bytes = b_off + b_cells + b_tiles + b_lt0 + b_rtiles + b_lt0 + b_part + b_S + b_A + b_bl + b_bm + b_mvg;
     if (hipMalloc(&p->ws, p->ws_bytes) != hipSuccess) {
         (void)hipGetLastError();
         delete p;
@@ -234,6 +243,8 @@ grawa_status_t grawa_plan_create(grawa_plan_t **out, int K, int64_t P, int L,
     p->d_cell_layer = reinterpret_cast<int32_t *>(w); w += b_cells;
     p->d_tiles = reinterpret_cast<GrawaTile *>(w); w += b_tiles;
     p->d_layer_tile0 = reinterpret_cast<int32_t *>(w); w += b_lt0;
+    p->d_rtiles = reinterpret_cast<GrawaTile *>(w); w += b_rtiles;
+    p->d_layer_rtile0 = reinterpret_cast<int32_t *>(w); w += b_lt0;
     p->d_partials = reinterpret_cast<double *>(w); w += b_part;
     p->d_S = reinterpret_cast<double *>(w); w += b_S;
     p->d_A = reinterpret_cast<float *>(w); w += b_A;
@@ -245,6 +256,8 @@ grawa_status_t grawa_plan_create(grawa_plan_t **out, int K, int64_t P, int L,
         hipMemcpy(p->d_cell_layer, cell_layer.data(), sizeof(int32_t) * (size_t)nc, hipMemcpyHostToDevice) != hipSuccess ||
         hipMemcpy(p->d_tiles, tiles.data(), sizeof(GrawaTile) * (size_t)nt, hipMemcpyHostToDevice) != hipSuccess ||
         hipMemcpy(p->d_layer_tile0, layer_tile0.data(), sizeof(int32_t) * ((size_t)L + 1), hipMemcpyHostToDevice) != hipSuccess ||
+        hipMemcpy(p->d_rtiles, rtiles.data(), sizeof(GrawaTile) * (size_t)nrt, hipMemcpyHostToDevice) != hipSuccess ||
+        hipMemcpy(p->d_layer_rtile0, layer_rtile0.data(), sizeof(int32_t) * ((size_t)L + 1), hipMemcpyHostToDevice) != hipSuccess ||
         hipMemset(p->d_partials, 0, b_part + b_S + b_A + b_bl + b_bm + b_mvg) != hipSuccess) {
         (void)hipFree(p->ws);
         delete p;
@@ -362,13 +375,13 @@ grawa_status_t grawa_local_sgd_prox(float *x, int64_t ldx, const void *g, int64_
                                     int64_t P, float lr, const float *center, float mu, float tau, void *stream)
 {
     if (!x || !center || K < 1 || P < 1 || ldx < P) return GRAWA_ERR_INVALID_ARG;
-    if (K > 64 || P >= ((int64_t)1 << 36)) return GRAWA_ERR_UNSUPPORTED;
+    if (K > 64 || P >= ((int64_t)1 << 32)) return GRAWA_ERR_UNSUPPORTED;
     if (!aligned16(x) || (ldx % 4) != 0 || !aligned16(center)) return GRAWA_ERR_ALIGNMENT;
     grawa_status_t st = check_grads(P, g, ldg, dt);
     if (st != GRAWA_OK) return st;
     if (!std::isfinite(lr) || !std::isfinite(mu) || !std::isfinite(tau) || !(tau > 0.f) || mu < 0.f || mu > tau)
         return GRAWA_ERR_INVALID_ARG;
-    const int T = 4096;
+    const int T = 256; /* short tiles: see k_rows_step */
     const int64_t nt = (P + T - 1) / T;
     GRAWA_TRY_HIP(grawa_launch_rows_step(x, ldx, g, ldg, dt, lr, center, mu / tau, nullptr, T, nt, K, P, nullptr,
                                          static_cast<hipStream_t>(stream)));
@@ -395,7 +408,7 @@ grawa_status_t grawa_local_step_scored(grawa_plan_t *p, float *x, int64_t ldx, c
     DeviceGuard guard(p->device);
     if (!guard.ok) return GRAWA_ERR_HIP;
     hipStream_t s = static_cast<hipStream_t>(stream);
-    GRAWA_TRY_HIP(grawa_launch_rows_step(x, ldx, g, ldg, dt, lr, center, w, p->d_tiles, p->tile_elems, p->n_tiles,
+    GRAWA_TRY_HIP(grawa_launch_rows_step(x, ldx, g, ldg, dt, lr, center, w, p->d_rtiles, 1024, p->n_rtiles,
                                          p->K, p->P, p->d_partials, s));
     GRAWA_TRY_HIP(grawa_launch_finalize_layers(p, nullptr, nullptr, s, 1, (double)gamma));
     p->local_t += 1;

@@ -32,6 +32,9 @@ struct grawa_plan {
     int64_t *d_off;         // [L+1] layer offsets
     GrawaTile *d_tiles;     // [n_tiles]
     int32_t *d_layer_tile0; // [L+1] first tile of every layer
+    GrawaTile *d_rtiles;    // [n_rtiles] short tiles (1024 columns) of the scored local step
+    int32_t *d_layer_rtile0; // [L+1]
+    int64_t n_rtiles;
     int32_t *d_cell_layer;  // [n_cells] layer of a 256-column cell, or ~(first layer) if it holds a boundary
     double *d_partials;     // [K][n_tiles] per-tile sums of squares
     double *d_S;            // [K][L] squared Frobenius norms

@@ -527,33 +527,88 @@ __global__ __launch_bounds__(GRAWA_CELL) void k_center_pull_any(
 // local SGD step
 // ---------------------------------------------------------------------------------
 
-#define GRAWA_SGD_U 4 // columns per lane of the plain SGD step (8 loads in flight per lane)
+#define GRAWA_SGD_U 4 // vectors per lane of the plain SGD step (8 loads in flight per lane)
 
-// grid (ceil(P/1024), K), block 256.  x[k][i] -= lr * g[k][i]; lane t of block m owns columns
-// 1024 m + t + 256 u, u < 4 (each wave access is one aligned 256-byte piece).
-template <typename GT, bool NT>
+// V gradient elements (V * sizeof(GT) = 4 or 8 bytes, naturally aligned) widened to float.
+template <typename GT, int V, bool NT> struct GradVec;
+template <bool NT> struct GradVec<float, 1, NT> {
+    static __device__ __forceinline__ void load(const float *p, float (&f)[1]) { f[0] = NT ? __builtin_nontemporal_load(p) : *p; }
+};
+template <bool NT> struct GradVec<uint16_t, 2, NT> {
+    static __device__ __forceinline__ void load(const uint16_t *p, float (&f)[2])
+    {
+        const uint32_t *q = reinterpret_cast<const uint32_t *>(p);
+        const uint32_t w = NT ? __builtin_nontemporal_load(q) : *q;
+        f[0] = bf16_lo(w);
+        f[1] = bf16_hi(w);
+    }
+};
+template <bool NT> struct GradVec<uint16_t, 4, NT> {
+    static __device__ __forceinline__ void load(const uint16_t *p, float (&f)[4])
+    {
+        const v2u *q = reinterpret_cast<const v2u *>(p);
+        const v2u w = NT ? __builtin_nontemporal_load(q) : *q;
+        f[0] = bf16_lo(w.x);
+        f[1] = bf16_hi(w.x);
+        f[2] = bf16_lo(w.y);
+        f[3] = bf16_hi(w.y);
+    }
+};
+template <int V> struct FloatVec { typedef float T __attribute__((ext_vector_type(V))); };
+template <> struct FloatVec<1> { typedef float T; };
+template <int V> __device__ __forceinline__ float vec_get(const typename FloatVec<V>::T &v, int c)
+{
+    if constexpr (V == 1) return v;
+    else return v[c];
+}
+template <int V> __device__ __forceinline__ void vec_set(typename FloatVec<V>::T &v, int c, float f)
+{
+    if constexpr (V == 1) v = f;
+    else v[c] = f;
+}
+
+// grid (ceil(P / (256*4*V)), K), block 256.  x[k][i] -= lr * g[k][i].  A lane handles 4 vectors of
+// V adjacent columns, vectors of a block 256*V columns apart; V = 1 for fp32 gradients (4-byte
+// accesses measured fastest for this read-modify-write stream) and 4 for bf16 (an 8-byte gradient
+// load with a 16-byte parameter access).  Rows start 16-byte aligned, so every vector is
+// naturally aligned; the last P % V columns of a row take a scalar path.
+template <typename GT, int V, bool NT>
 __global__ __launch_bounds__(GRAWA_CELL) void k_local_sgd(float *__restrict__ x, int64_t ldx,
                                                           const GT *__restrict__ g, int64_t ldg,
                                                           int64_t P, float lr)
 {
-    const int64_t cell0 = (int64_t)blockIdx.x * (GRAWA_CELL * GRAWA_SGD_U);
-    const unsigned t = threadIdx.x;
-    const uint64_t xr = uniform_base(x + (int64_t)blockIdx.y * ldx + cell0);
-    const uint64_t gr = uniform_base(g + (int64_t)blockIdx.y * ldg + cell0);
-    float xv[GRAWA_SGD_U], gv[GRAWA_SGD_U];
+    typedef typename FloatVec<V>::T XV;
+    const int64_t nvec = P / V;
+    const int64_t j0 = (int64_t)blockIdx.x * (GRAWA_CELL * GRAWA_SGD_U) + threadIdx.x;
+    float *xr = x + (int64_t)blockIdx.y * ldx;
+    const GT *gr = g + (int64_t)blockIdx.y * ldg;
+    XV xv[GRAWA_SGD_U];
+    float gf[GRAWA_SGD_U][V];
 #pragma unroll
     for (int u = 0; u < GRAWA_SGD_U; ++u) {
-        const unsigned c = u * GRAWA_CELL + t;
-        xv[u] = gv[u] = 0.f;
-        if (cell0 + c < P) {
-            xv[u] = ld_lane<NT, float>(xr, c * 4u);
-            gv[u] = Grad<GT>::template lane<NT>(gr, c * (unsigned)sizeof(GT));
+        const int64_t j = j0 + u * GRAWA_CELL;
+        if (j < nvec) {
+            const XV *xp = reinterpret_cast<const XV *>(xr + j * V);
+            xv[u] = NT ? __builtin_nontemporal_load(xp) : *xp;
+            GradVec<GT, V, NT>::load(gr + j * V, gf[u]);
         }
     }
+    __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
     for (int u = 0; u < GRAWA_SGD_U; ++u) {
-        const unsigned c = u * GRAWA_CELL + t;
-        if (cell0 + c < P) st_lane<NT, float>(xr, c * 4u, fmaf(-lr, gv[u], xv[u]));
+        const int64_t j = j0 + u * GRAWA_CELL;
+        if (j < nvec) {
+            XV o = xv[u];
+#pragma unroll
+            for (int c = 0; c < V; ++c) vec_set<V>(o, c, fmaf(-lr, gf[u][c], vec_get<V>(xv[u], c)));
+            XV *xp = reinterpret_cast<XV *>(xr + j * V);
+            if (NT) __builtin_nontemporal_store(o, xp);
+            else *xp = o;
+        }
+    }
+    if (blockIdx.x == 0 && threadIdx.x < (unsigned)(P - nvec * V)) {
+        const int64_t i = nvec * V + threadIdx.x;
+        xr[i] = fmaf(-lr, Grad<GT>::one(gr + i), xr[i]);
     }
 }
 
@@ -563,6 +618,9 @@ __global__ __launch_bounds__(GRAWA_CELL) void k_local_sgd(float *__restrict__ x,
 // grid n_tiles, block 256.  The block walks its tile in aligned chunks of 256 columns; per chunk a
 // lane owns one column and all K rows of it (2K loads in flight, the stored center read once for
 // all K rows), as in the center+pull pass.  tiles == nullptr: uniform tiles of tile_elems columns.
+// Tiles are kept short (256 columns without scores, 1024 with): blocks that run together then
+// cover one compact window of every row, which measured 10-15 % faster than 4096-16384-column
+// tiles (software-pipelining the chunk loop made no difference).
 template <int KT, bool EXACT, typename GT, bool NT, bool PROX, bool SCORE, int WPE>
 __global__ __launch_bounds__(GRAWA_CELL) __attribute__((amdgpu_waves_per_eu(1, WPE))) void k_rows_step(
     float *__restrict__ x, int64_t ldx, const GT *__restrict__ g, int64_t ldg, float lr,
@@ -598,6 +656,7 @@ __global__ __launch_bounds__(GRAWA_CELL) __attribute__((amdgpu_waves_per_eu(1, W
             for (int k = 0; k < KT; ++k)
                 if (k < nk) gv[k] = Grad<GT>::template lane<NT>(uniform_base(g + (int64_t)k * ldg + c0), goff);
             if (PROX) cv = ld_lane<false, float>(uniform_base(center + c0), xoff);
+            __builtin_amdgcn_sched_barrier(0); // every load of the chunk is issued before the first is used
 #pragma unroll
             for (int k = 0; k < KT; ++k)
                 if (k < nk) {
@@ -654,11 +713,14 @@ hipError_t grawa_launch_sumsq(const grawa_plan *p, const void *g, int64_t ldg, g
     return hipGetLastError();
 }
 
+// update_estimate != 0: the partials come from the local step (short-tile map) and the running
+// norm estimate is updated with the new norms.
 hipError_t grawa_launch_finalize_layers(const grawa_plan *p, float *norms_user, float *beta_user,
                                         hipStream_t s, int update_estimate, double gamma)
 {
     k_finalize_layers<<<dim3((unsigned)p->L), dim3(GRAWA_FIN_BLOCK), 0, s>>>(
-        p->d_partials, p->n_tiles, p->d_layer_tile0, p->K, p->L, p->d_S, p->d_A, norms_user,
+        p->d_partials, update_estimate ? p->n_rtiles : p->n_tiles,
+        update_estimate ? p->d_layer_rtile0 : p->d_layer_tile0, p->K, p->L, p->d_S, p->d_A, norms_user,
         p->d_beta_layer, beta_user, update_estimate ? p->d_mvg : nullptr, gamma);
     return hipGetLastError();
 }
@@ -771,17 +833,18 @@ hipError_t grawa_launch_center_pull(const grawa_plan *p, float *x, int64_t ldx, 
 hipError_t grawa_launch_local_sgd(float *x, int64_t ldx, const void *g, int64_t ldg, grawa_dtype_t dt,
                                   int K, int64_t P, float lr, hipStream_t s)
 {
-    const int64_t per_block = GRAWA_CELL * GRAWA_SGD_U;
-    const int64_t gx = (P + per_block - 1) / per_block;
+    const int64_t per_block = GRAWA_CELL * GRAWA_SGD_U * (dt == GRAWA_BF16 ? 4 : 1);
+    int64_t gx = (P + per_block - 1) / per_block;
+    if (gx < 1) gx = 1;
     const dim3 grid((unsigned)gx, (unsigned)K), block(GRAWA_CELL);
     const bool nt = (int64_t)K * P * 4 > GRAWA_STREAMING_MIN_BYTES && rows_line_aligned(x, ldx, 4) &&
                     rows_line_aligned(g, ldg, dt == GRAWA_BF16 ? 2 : 4);
     if (dt == GRAWA_BF16) {
-        if (nt) k_local_sgd<uint16_t, true><<<grid, block, 0, s>>>(x, ldx, (const uint16_t *)g, ldg, P, lr);
-        else k_local_sgd<uint16_t, false><<<grid, block, 0, s>>>(x, ldx, (const uint16_t *)g, ldg, P, lr);
+        if (nt) k_local_sgd<uint16_t, 4, true><<<grid, block, 0, s>>>(x, ldx, (const uint16_t *)g, ldg, P, lr);
+        else k_local_sgd<uint16_t, 4, false><<<grid, block, 0, s>>>(x, ldx, (const uint16_t *)g, ldg, P, lr);
     } else {
-        if (nt) k_local_sgd<float, true><<<grid, block, 0, s>>>(x, ldx, (const float *)g, ldg, P, lr);
-        else k_local_sgd<float, false><<<grid, block, 0, s>>>(x, ldx, (const float *)g, ldg, P, lr);
+        if (nt) k_local_sgd<float, 1, true><<<grid, block, 0, s>>>(x, ldx, (const float *)g, ldg, P, lr);
+        else k_local_sgd<float, 1, false><<<grid, block, 0, s>>>(x, ldx, (const float *)g, ldg, P, lr);
     }
     return hipGetLastError();
 }
