@@ -168,3 +168,55 @@ def test_config3_transformer_bf16(variant):
 
 def test_config4_resnet50_fused_sgd():
     run_full(4, "lgrawa", full_compare=False)
+
+
+def test_config2_local_round_full_size():
+    """Appendix G round at the size of configuration 2: two scored local steps with the proximity
+    step, then the LGRAWA communication from the running estimate.  Estimate and weight tables are
+    compared in full, parameters on sampled windows."""
+    w = W.config(2)
+    P, K, L = w.P, w.K, w.L
+    lr, lam, gamma, mu, tau = 0.05, w.lam, 0.9, 0.05, 16.0
+    say("config 2 local round K=%d L=%d P=%d" % (K, L, P))
+    x, g1 = W.make_inputs(w, device=DEV)
+    w2 = W.config(2)
+    w2.seed = (0, 22)
+    _, g2 = W.make_inputs(w2, device=DEV)
+    x0 = x.clone()
+    cprev = 0.05 * torch.randn(W.round_up(P, 256), device=DEV, generator=torch.Generator(device=DEV).manual_seed(3))
+    cen = torch.empty(W.round_up(P, 4), device=DEV)
+    wts = torch.empty((K, L), device=DEV)
+    est = torch.empty((K, L), device=DEV)
+    with grawa.Plan(K, P, w.offsets) as plan:
+        plan.local_step_scored(x[:, :P], g1[:, :P], lr, gamma, center=cprev, mu=mu, tau=tau)
+        plan.local_step_scored(x[:, :P], g2[:, :P], lr, gamma, center=cprev, mu=mu, tau=tau)
+        plan.local_lgrawa_update(x[:, :P], lam, center_out=cen, weights_out=wts, est_out=est)
+        torch.cuda.synchronize()
+    say("gpu done; reference estimate")
+    sc = orc.LocalScores(K, L, gamma)
+    sc.step(W.to_numpy_grads(g1), w.offsets)
+    sc.step(W.to_numpy_grads(g2), w.offsets)
+    assert_table_close(est.cpu().numpy(), sc.g_est, TIGHT, "g_est")
+    beta = sc.weights("lgrawa")
+    assert_table_close(wts.cpu().numpy(), beta, TIGHT, "beta")
+    rng = np.random.default_rng(5)
+    off = w.offsets
+    for i0 in sample_windows(w, rng, n_random=12):
+        i1 = min(P, i0 + WINDOW)
+        xs = np.ascontiguousarray(x0[:, i0:i1].cpu().numpy())
+        gs = [W.to_numpy_grads(g[:, i0:i1].contiguous()) for g in (g1, g2)]
+        cp = cprev[i0:i1].cpu().numpy().astype(np.float64)
+        cur = orc.local_sgd(xs, gs[0], lr, prox_center=cp, mu=mu, tau=tau)
+        # second step from the float64 state: x - lr g, then the proximity step
+        from parity_util import grads_to_f64
+        cur = cur - lr * grads_to_f64(gs[1])
+        cur = (1.0 - mu / tau) * cur + (mu / tau) * cp
+        l0 = int(np.searchsorted(off, i0, side="right") - 1)
+        l1 = int(np.searchsorted(off, i1, side="left"))
+        layer_of = np.repeat(np.arange(l0, l1), np.diff(np.clip(off[l0:l1 + 1], i0, i1)))
+        c = (beta[:, layer_of] * cur).sum(axis=0)
+        want = (1.0 - lam) * cur + lam * c
+        scale = np.maximum((np.abs(xs.astype(np.float64)) + lr * (np.abs(grads_to_f64(gs[0])) + np.abs(grads_to_f64(gs[1])))).max(axis=0), np.abs(cp))
+        assert_params_close(x[:, i0:i1].cpu().numpy(), want, off, TIGHT, "x window %d" % i0, scale, col0=i0)
+        assert_params_close(cen[i0:i1].cpu().numpy(), c, off, TIGHT, "center window %d" % i0, scale, col0=i0)
+    assert torch.equal(x[:, P:], x0[:, P:])
