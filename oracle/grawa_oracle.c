@@ -17,7 +17,8 @@
  * unnumbered display after eq. (2); MGRAWA, Sec. 5.1 eqs. (3)-(4); LGRAWA,
  * Sec. 5.2 eqs. (5)-(7); local SGD step and its place before the distributed
  * phase, Algorithms 1 and 2; proximity step, same algorithms; running estimate of the
- * norm scores, Appendix G (Local MGRAWA/LGRAWA algorithm).
+ * norm scores, Appendix G (Local MGRAWA/LGRAWA algorithm); Nesterov-momentum local optimizer,
+ * Appendix B.2.2; EASGD and LSGD centers, Appendix F.
  *
  * Every function returns 0 on success, nonzero on a bad argument.
  */
@@ -223,4 +224,52 @@ int oracle_sum_layers(const double *est, int64_t K, int64_t L, double *A)
         A[m] = a;
     }
     return 0;
+}
+
+/* Local optimizer of the experiments (Appendix B.2.2: SGD, momentum, Nesterov acceleration,
+ * weight decay), one step on a chunk.  The paper names the method but prints no formula; the
+ * reading taken is the usual framework form of Nesterov's accelerated gradient,
+ *     d   = grad + wd * x
+ *     buf <- momentum * buf + d
+ *     x   <- x - eta * (d + momentum * buf)
+ * whose iterates are the look-ahead points x_t + momentum * v_t of the classical two-line form
+ * v <- momentum v - eta grad(x + momentum v), x <- x + v  (a test checks that equivalence).
+ * xd, buf: chunks [K][n] for columns i0..; g: the whole gradient array [K][ldg]. */
+int oracle_nesterov_sgd(double *xd, double *buf, int64_t K, int64_t n, int64_t i0, const void *g,
+                        int dtype, int64_t ldg, double eta, double momentum, double wd)
+{
+    if (!xd || !buf || !g || K < 1 || n < 0 || i0 < 0 || ldg < i0 + n) return 1;
+    for (int64_t m = 0; m < K; ++m)
+        for (int64_t i = 0; i < n; ++i) {
+            double d = widen_at(g, dtype, m * ldg + i0 + i) + wd * xd[m * n + i];
+            buf[m * n + i] = momentum * buf[m * n + i] + d;
+            xd[m * n + i] = xd[m * n + i] - eta * (d + momentum * buf[m * n + i]);
+        }
+    return 0;
+}
+
+/* EASGD center (Appendix F, first algorithm), on a chunk: the workers' plain average x_a, then
+ * the moving average in time  x_C <- (1 - rho) x_C + rho x_a.  The printed line reads
+ * "(1 - rho) x_a + rho x_a", which is a no-op; the text (center = average of the workers "both
+ * in space and time") fixes the reading with the previous center on the left. */
+int oracle_easgd_center(const double *xd, int64_t K, int64_t n, double *c, double rho)
+{
+    if (!xd || !c || K < 1 || n < 0) return 1;
+    for (int64_t i = 0; i < n; ++i) {
+        double s = 0.0;
+        for (int64_t m = 0; m < K; ++m) s += xd[m * n + i];
+        c[i] = (1.0 - rho) * c[i] + rho * (s / (double)K);
+    }
+    return 0;
+}
+
+/* LSGD leader (Appendix F, second algorithm): index of the worker with the smallest loss
+ * (the first one on ties).  Returns -1 on a bad argument. */
+int64_t oracle_leader(const double *loss, int64_t K)
+{
+    if (!loss || K < 1) return -1;
+    int64_t best = 0;
+    for (int64_t m = 1; m < K; ++m)
+        if (loss[m] < loss[best]) best = m;
+    return best;
 }

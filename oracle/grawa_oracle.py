@@ -68,6 +68,12 @@ def _bind(L):
     L.oracle_prox.argtypes = [vp, i64, i64, vp, dbl, dbl]
     L.oracle_norm_momentum.argtypes = [vp, vp, vp, i64, dbl, i64]
     L.oracle_sum_layers.argtypes = [vp, i64, i64, vp]
+    L.oracle_nesterov_sgd.argtypes = [vp, vp, i64, i64, i64, vp, it, i64, dbl, dbl, dbl]
+    L.oracle_nesterov_sgd.restype = it
+    L.oracle_easgd_center.argtypes = [vp, i64, i64, vp, dbl]
+    L.oracle_easgd_center.restype = it
+    L.oracle_leader.argtypes = [vp, i64]
+    L.oracle_leader.restype = i64
     for name in ("oracle_norm_momentum", "oracle_sum_layers", "oracle_sumsq", "oracle_layer_norms", "oracle_model_norms", "oracle_weights",
                  "oracle_load_params", "oracle_local_sgd", "oracle_center", "oracle_pull",
                  "oracle_prox"):
@@ -334,3 +340,58 @@ def local_grawa_round(x, grads, off, lr, lam, gamma, policy, *, prox_center=None
     _ok(Lb.oracle_pull(_p(xd), K, P, _p(c), float(lam)), "pull")
     sc.reset()
     return {"x": xd, "center": c, "beta": beta, "g_est": est}
+
+
+# ----------------------------------------------------------------------------
+# Local optimizer of the experiments and the competing centers
+# ----------------------------------------------------------------------------
+
+def nesterov_sgd(x, buf, g, lr, momentum, wd=0.0, *, P=None, _lib=None):
+    """One Nesterov-momentum SGD step with weight decay (Appendix B.2.2).  x: float32 [K, ld] or
+    float64 [K, P]; buf: float64 [K, P] momentum buffer (zeros at the start).
+    Returns (x_new float64 [K, P], buf_new float64 [K, P]); the inputs are not modified."""
+    Lb = _lib or lib()
+    g, gdt = _grads(g)
+    x = np.asarray(x)
+    K = x.shape[0]
+    P = min(x.shape[1], g.shape[1]) if P is None else P
+    xd = np.ascontiguousarray(x[:, :P], dtype=np.float64).copy()
+    bd = np.ascontiguousarray(buf, dtype=np.float64).copy()
+    if bd.shape != (K, P):
+        raise ValueError("buf must be [K, P]")
+    _ok(Lb.oracle_nesterov_sgd(_p(xd), _p(bd), K, P, 0, _p(g), gdt, g.shape[1], float(lr), float(momentum),
+                               float(wd)), "nesterov_sgd")
+    return xd, bd
+
+
+def easgd_update(x, center, lam, rho, *, P=None, _lib=None):
+    """EASGD distributed phase (Appendix F): x_a = mean of the workers, x_C <- (1-rho) x_C + rho x_a,
+    then the pull of every worker toward x_C.  Returns (x_new float64 [K, P], center_new [P])."""
+    Lb = _lib or lib()
+    x = _params(x)
+    K = x.shape[0]
+    P = x.shape[1] if P is None else P
+    xd = np.empty((K, P), dtype=np.float64)
+    _ok(Lb.oracle_load_params(_p(x), K, x.shape[1], 0, P, _p(xd)), "load_params")
+    c = np.ascontiguousarray(np.asarray(center, dtype=np.float64)[:P]).copy()
+    _ok(Lb.oracle_easgd_center(_p(xd), K, P, _p(c), float(rho)), "easgd_center")
+    _ok(Lb.oracle_pull(_p(xd), K, P, _p(c), float(lam)), "pull")
+    return xd, c
+
+
+def lsgd_update(x, losses, lam, *, P=None, _lib=None):
+    """LSGD distributed phase (Appendix F): the center is the worker with the smallest loss; every
+    worker is pulled toward it.  Returns (x_new float64 [K, P], leader index)."""
+    Lb = _lib or lib()
+    x = _params(x)
+    K = x.shape[0]
+    P = x.shape[1] if P is None else P
+    losses = np.ascontiguousarray(losses, dtype=np.float64)
+    if losses.shape != (K,):
+        raise ValueError("losses must be [K]")
+    lead = int(Lb.oracle_leader(_p(losses), K))
+    xd = np.empty((K, P), dtype=np.float64)
+    _ok(Lb.oracle_load_params(_p(x), K, x.shape[1], 0, P, _p(xd)), "load_params")
+    c = xd[lead].copy()
+    _ok(Lb.oracle_pull(_p(xd), K, P, _p(c), float(lam)), "pull")
+    return xd, lead

@@ -46,6 +46,13 @@ MUTANTS = [
     ("bias_correction_missing", "g_est[i] = gamma * g_mvg[i] / denom;", "g_est[i] = gamma * g_mvg[i];"),
     ("bias_correction_wrong_power", "double denom = 1.0 - pow(gamma, (double)t);", "double denom = 1.0 - pow(gamma, (double)(t + 1));"),
     ("estimate_without_leading_gamma", "g_est[i] = gamma * g_mvg[i] / denom;", "g_est[i] = g_mvg[i] / denom;"),
+    ("nesterov_without_lookahead", "xd[m * n + i] = xd[m * n + i] - eta * (d + momentum * buf[m * n + i]);", "xd[m * n + i] = xd[m * n + i] - eta * buf[m * n + i];"),
+    ("nesterov_decay_dropped", "+ wd * xd[m * n + i];", ";"),
+    ("nesterov_buffer_dampened", "buf[m * n + i] = momentum * buf[m * n + i] + d;", "buf[m * n + i] = momentum * buf[m * n + i] + (1.0 - momentum) * d;"),
+    ("easgd_center_is_a_noop", "c[i] = (1.0 - rho) * c[i] + rho * (s / (double)K);", "c[i] = (1.0 - rho) * (s / (double)K) + rho * (s / (double)K);"),
+    ("easgd_sum_not_mean", "rho * (s / (double)K);", "rho * s;"),
+    ("leader_is_largest_loss", "if (loss[m] < loss[best]) best = m;", "if (loss[m] > loss[best]) best = m;"),
+    ("leader_last_on_ties", "if (loss[m] < loss[best]) best = m;", "if (loss[m] <= loss[best]) best = m;"),
     ("layer_sum_skips_first", "for (int64_t k = 0; k < L; ++k) a += est[m * L + k];", "for (int64_t k = 1; k < L; ++k) a += est[m * L + k];"),
 ]
 

@@ -559,3 +559,93 @@ def test_local_grawa_round_several_steps():
     np.testing.assert_allclose(r["g_est"], est, rtol=1e-13)
     np.testing.assert_allclose(r["beta"], beta, rtol=1e-13)
     np.testing.assert_allclose(r["x"], want, rtol=1e-11, atol=1e-15)
+
+
+# ----------------------------------------------------------------------------
+# Nesterov-momentum local optimizer (Appendix B.2.2) and the competing centers (Appendix F)
+# ----------------------------------------------------------------------------
+
+def test_nesterov_matches_the_classical_two_line_form():
+    # classical NAG on f(x) = a x^2 / 2 in exact rationals: v <- mu v - eta f'(x + mu v), x <- x + v.
+    # The framework form fed with the gradient at its own iterate must walk the look-ahead points y = x + mu v.
+    a, mu, eta = Fr(3, 2), Fr(9, 10), Fr(1, 10)
+    xc, v = Fr(4), Fr(0)
+    y = [xc + mu * v]
+    for _ in range(6):
+        v = mu * v - eta * a * (xc + mu * v)
+        xc = xc + v
+        y.append(xc + mu * v)
+    x = np.array([[float(y[0])]], dtype=np.float32)          # 4.0 is exact in fp32
+    buf = np.zeros((1, 1))
+    cur = x.astype(np.float64)
+    for t in range(6):
+        g = (float(a) * cur).astype(np.float64)
+        # feed the gradient through the fp32 interface exactly: use a power-of-two friendly check instead
+        g32 = g.astype(np.float32)
+        cur, buf = orc.nesterov_sgd(cur, buf, g32, float(eta), float(mu))
+        assert cur[0, 0] == pytest.approx(float(y[t + 1]), rel=2e-6)       # fp32 rounding of the fed gradient only
+
+
+def test_nesterov_special_cases_and_closed_forms():
+    rng = np.random.default_rng(9)
+    x = rng.standard_normal((3, 50)).astype(np.float32)
+    g = rng.standard_normal((3, 56)).astype(np.float32)
+    z = np.zeros((3, 50))
+    # no momentum, no decay: the plain SGD step, and the buffer holds the gradient
+    xn, bn = orc.nesterov_sgd(x, z, g, 0.1, 0.0)
+    np.testing.assert_array_equal(xn, orc.local_sgd(x, g, 0.1, P=50))
+    np.testing.assert_array_equal(bn, g[:, :50].astype(np.float64))
+    # constant gradient: buf_t = g (1 - mu^t)/(1 - mu); x_t = x_0 - eta sum_s (g + mu buf_s)
+    mu, eta = 0.5, 0.25
+    cur, buf = x.astype(np.float64), z
+    gd = g[:, :50].astype(np.float64)
+    acc = np.zeros_like(gd)
+    for t in range(1, 6):
+        cur, buf = orc.nesterov_sgd(cur, buf, g, eta, mu)
+        np.testing.assert_allclose(buf, gd * (1 - mu ** t) / (1 - mu), rtol=1e-14)
+        acc += gd + mu * gd * (1 - mu ** t) / (1 - mu)
+        np.testing.assert_allclose(cur, x.astype(np.float64) - eta * acc, rtol=1e-12, atol=1e-15)
+    # weight decay alone from a zero buffer: x <- x (1 - eta wd (1 + mu))
+    g0 = np.zeros_like(g)
+    xn, bn = orc.nesterov_sgd(x, z, g0, 0.1, 0.9, 5e-4)
+    np.testing.assert_allclose(xn, x.astype(np.float64) * (1 - 0.1 * 5e-4 * 1.9), rtol=1e-14)
+    np.testing.assert_allclose(bn, 5e-4 * x.astype(np.float64), rtol=1e-14)
+    # bf16 gradients are widened exactly
+    from parity_util import grads_to_f64
+    gb = _bf16_bits(g)
+    xn, _ = orc.nesterov_sgd(x, z, gb, 0.1, 0.0)
+    np.testing.assert_array_equal(xn, x.astype(np.float64) - 0.1 * grads_to_f64(gb)[:, :50])
+
+
+def test_easgd_center_and_pull():
+    rng = np.random.default_rng(10)
+    x = rng.integers(-8, 9, size=(4, 7)).astype(np.float32)
+    c0 = rng.integers(-8, 9, size=7).astype(np.float64)
+    rho, lam = Fr(1, 4), Fr(1, 2)
+    mean = [sum(Fr(int(v)) for v in x[:, i]) / 4 for i in range(7)]
+    c = [(1 - rho) * Fr(int(c0[i])) + rho * mean[i] for i in range(7)]
+    want = [[(1 - lam) * Fr(int(x[m, i])) + lam * c[i] for i in range(7)] for m in range(4)]
+    xn, cn = orc.easgd_update(x, c0, float(lam), float(rho))
+    np.testing.assert_array_equal(cn, as_float(c))
+    np.testing.assert_array_equal(xn, np.array([as_float(r) for r in want]))
+    # rho = 1: the center is the plain average, i.e. GRAWA with equal weights; rho = 0: the old center stays
+    xn1, cn1 = orc.easgd_update(x, c0, 0.5, 1.0)
+    xr, cr = orc.center_pull(x, np.full(4, 0.25), [0, 7], 0.5)
+    np.testing.assert_allclose(cn1, cr, rtol=1e-15)
+    np.testing.assert_allclose(xn1, xr, rtol=1e-15)
+    _, cn0 = orc.easgd_update(x, c0, 0.5, 0.0)
+    np.testing.assert_array_equal(cn0, c0)
+
+
+def test_lsgd_leader_and_pull():
+    rng = np.random.default_rng(11)
+    x = rng.standard_normal((5, 9)).astype(np.float32)
+    losses = np.array([0.7, 0.2, 0.9, 0.2, 0.5])
+    xn, lead = orc.lsgd_update(x, losses, 0.25)
+    assert lead == 1                                         # smallest loss, first on ties
+    hot = np.zeros(5)
+    hot[1] = 1.0
+    xr, cr = orc.center_pull(x, hot, [0, 9], 0.25)           # one-hot weights through the GRAWA center
+    np.testing.assert_array_equal(cr, x[1].astype(np.float64))
+    np.testing.assert_allclose(xn, xr, rtol=1e-15)
+    np.testing.assert_array_equal(xn[1], x[1].astype(np.float64))   # the leader does not move
