@@ -206,6 +206,41 @@ grawa_status_t grawa_local_mgrawa_update(grawa_plan_t *plan, float *x, int64_t l
 grawa_status_t grawa_local_scores_reset(grawa_plan_t *plan, void *stream);
 
 /*
+ * Local optimizer of the experiments (Appendix B.2.2: SGD with momentum, Nesterov
+ * acceleration and weight decay), one step for every worker.  The paper names the
+ * method without printing it; the form computed is
+ *   d = g_k + weight_decay x_k ;  buf_k <- momentum buf_k + d ;
+ *   x_k <- x_k - lr (d + momentum buf_k)
+ * whose iterates are the look-ahead points of Nesterov's accelerated gradient.
+ * buf: device float [K][ldb], the momentum buffer, updated in place; the caller
+ * zeroes it before the first step and keeps it between steps.  buf and ldb obey
+ * the rules of x and ldx (16-byte aligned base, ldb % 4 == 0, ldb >= P).
+ * momentum >= 0, weight_decay >= 0, all finite.  Needs no plan.
+ */
+grawa_status_t grawa_local_nesterov(float *x, int64_t ldx, const void *g, int64_t ldg,
+                                    grawa_dtype_t g_dtype, float *buf, int64_t ldb, int K, int64_t P,
+                                    float lr, float momentum, float weight_decay, void *stream);
+
+/*
+ * Distributed phase of the two competing center rules of Appendix F, on the same
+ * K x P layout and with the same pull  x_k <- (1-lambda) x_k + lambda x_C.
+ *
+ * grawa_easgd_update: x_a = (1/K) sum_k x_k ;  x_C <- (1 - rho) x_C + rho x_a
+ *   (the center is averaged over workers and over time; the line printed in the
+ *   appendix has x_a on both sides and is read with the previous center on the
+ *   left).  center: device float [P], 16-byte aligned, REQUIRED: previous center on
+ *   entry, new center on return.  0 <= rho <= 1.
+ *
+ * grawa_lsgd_update: x_C = x_k of the worker with the smallest loss (the first
+ *   one on ties).  losses: device float [K].  center_out (device float [P] or
+ *   NULL) receives x_C, leader_out (device int32 or NULL) the leader's index.
+ */
+grawa_status_t grawa_easgd_update(grawa_plan_t *plan, float *x, int64_t ldx, float lambda, float rho,
+                                  float *center, void *stream);
+grawa_status_t grawa_lsgd_update(grawa_plan_t *plan, float *x, int64_t ldx, const float *losses,
+                                 float lambda, float *center_out, int *leader_out, void *stream);
+
+/*
  * Measurement aids (not part of the method).
  *
  * grawa_plan_profile: with enable != 0 the plan attaches a start and a stop

@@ -120,7 +120,7 @@ grawa_status_t run_update(grawa_plan *p, float *x, int64_t ldx, const void *g, i
 
     GRAWA_TRY_HIP(grawa_launch_center_pull(p, x, ldx, per_layer ? p->d_beta_layer : p->d_beta_model,
                                            per_layer, lambda, g_sgd, ldg_sgd, dt, lr, fuse_sgd,
-                                           center_out, s, prof ? ev[2] : nullptr, prof ? ev[3] : nullptr));
+                                           center_out, 0.f, 0, s, prof ? ev[2] : nullptr, prof ? ev[3] : nullptr));
     if (prof) p->profile_n += 1;
     return GRAWA_OK;
 }
@@ -350,7 +350,8 @@ grawa_status_t grawa_center_pull(grawa_plan_t *p, float *x, int64_t ldx, const f
     const bool prof = prof_active(p);
     hipEvent_t *ev = prof ? p->ev + 4 * (size_t)p->profile_n : nullptr;
     GRAWA_TRY_HIP(grawa_launch_center_pull(p, x, ldx, weights, per_layer ? 1 : 0, lambda, nullptr, 0, GRAWA_F32,
-                                           0.f, 0, center_out, s, prof ? ev[2] : nullptr, prof ? ev[3] : nullptr));
+                                           0.f, 0, center_out, 0.f, 0, s, prof ? ev[2] : nullptr,
+                                           prof ? ev[3] : nullptr));
     if (prof) {
         p->profile_pull_only = 1;
         p->profile_n += 1;
@@ -369,6 +370,55 @@ grawa_status_t grawa_local_sgd(float *x, int64_t ldx, const void *g, int64_t ldg
     if (!std::isfinite(lr)) return GRAWA_ERR_INVALID_ARG;
     GRAWA_TRY_HIP(grawa_launch_local_sgd(x, ldx, g, ldg, dt, K, P, lr, static_cast<hipStream_t>(stream)));
     return GRAWA_OK;
+}
+
+grawa_status_t grawa_local_nesterov(float *x, int64_t ldx, const void *g, int64_t ldg, grawa_dtype_t dt, float *buf,
+                                    int64_t ldb, int K, int64_t P, float lr, float momentum, float weight_decay,
+                                    void *stream)
+{
+    if (!x || !buf || K < 1 || P < 1 || ldx < P || ldb < P) return GRAWA_ERR_INVALID_ARG;
+    if (K > 65535 || P >= ((int64_t)1 << 32)) return GRAWA_ERR_UNSUPPORTED;
+    if (!aligned16(x) || (ldx % 4) != 0 || !aligned16(buf) || (ldb % 4) != 0) return GRAWA_ERR_ALIGNMENT;
+    grawa_status_t st = check_grads(P, g, ldg, dt);
+    if (st != GRAWA_OK) return st;
+    if (!std::isfinite(lr) || !std::isfinite(momentum) || !std::isfinite(weight_decay) || momentum < 0.f ||
+        weight_decay < 0.f)
+        return GRAWA_ERR_INVALID_ARG;
+    GRAWA_TRY_HIP(grawa_launch_nesterov(x, ldx, g, ldg, dt, buf, ldb, K, P, lr, momentum, weight_decay,
+                                        static_cast<hipStream_t>(stream)));
+    return GRAWA_OK;
+}
+
+/* EASGD and LSGD share the pull kernel: only the weights (and the moving center) differ. */
+static grawa_status_t run_fixed_center(grawa_plan_t *p, float *x, int64_t ldx, const float *loss, float lambda,
+                                       float rho, int moving, float *center, float *weights_out, int *leader_out,
+                                       void *stream)
+{
+    grawa_status_t st;
+    if ((st = check_params(p, x, ldx)) != GRAWA_OK) return st;
+    if ((st = check_lambda(lambda)) != GRAWA_OK) return st;
+    if ((st = check_center(center)) != GRAWA_OK) return st;
+    DeviceGuard guard(p->device);
+    if (!guard.ok) return GRAWA_ERR_HIP;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    GRAWA_TRY_HIP(grawa_launch_center_weights(p, loss, weights_out, leader_out, s));
+    GRAWA_TRY_HIP(grawa_launch_center_pull(p, x, ldx, p->d_beta_model, 0, lambda, nullptr, 0, GRAWA_F32, 0.f, 0,
+                                           center, rho, moving, s, nullptr, nullptr));
+    return GRAWA_OK;
+}
+
+grawa_status_t grawa_easgd_update(grawa_plan_t *p, float *x, int64_t ldx, float lambda, float rho, float *center,
+                                  void *stream)
+{
+    if (!center || !(rho >= 0.f && rho <= 1.f)) return GRAWA_ERR_INVALID_ARG;
+    return run_fixed_center(p, x, ldx, nullptr, lambda, rho, 1, center, nullptr, nullptr, stream);
+}
+
+grawa_status_t grawa_lsgd_update(grawa_plan_t *p, float *x, int64_t ldx, const float *losses, float lambda,
+                                 float *center_out, int *leader_out, void *stream)
+{
+    if (!losses) return GRAWA_ERR_INVALID_ARG;
+    return run_fixed_center(p, x, ldx, losses, lambda, 0.f, 0, center_out, nullptr, leader_out, stream);
 }
 
 grawa_status_t grawa_local_sgd_prox(float *x, int64_t ldx, const void *g, int64_t ldg, grawa_dtype_t dt, int K,
@@ -432,7 +482,7 @@ grawa_status_t local_update(grawa_plan_t *p, float *x, int64_t ldx, int per_laye
     const bool prof = prof_active(p);
     hipEvent_t *ev = prof ? p->ev + 4 * (size_t)p->profile_n : nullptr;
     GRAWA_TRY_HIP(grawa_launch_center_pull(p, x, ldx, per_layer ? p->d_beta_layer : p->d_beta_model, per_layer,
-                                           lambda, nullptr, 0, GRAWA_F32, 0.f, 0, center_out, s,
+                                           lambda, nullptr, 0, GRAWA_F32, 0.f, 0, center_out, 0.f, 0, s,
                                            prof ? ev[2] : nullptr, prof ? ev[3] : nullptr));
     if (prof) {
         p->profile_pull_only = 1;

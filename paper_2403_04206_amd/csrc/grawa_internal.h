@@ -68,7 +68,13 @@ hipError_t grawa_launch_finalize_model(const grawa_plan *p, grawa_norm_mode_t mo
 hipError_t grawa_launch_center_pull(const grawa_plan *p, float *x, int64_t ldx, const float *beta,
                                     int per_layer, float lambda, const void *g_sgd,
                                     int64_t ldg_sgd, grawa_dtype_t dt, float lr, int fuse_sgd,
-                                    float *center_out, hipStream_t s, hipEvent_t e0, hipEvent_t e1);
+                                    float *center_out, float rho, int moving, hipStream_t s, hipEvent_t e0,
+                                    hipEvent_t e1);
+hipError_t grawa_launch_nesterov(float *x, int64_t ldx, const void *g, int64_t ldg, grawa_dtype_t dt,
+                                 float *buf, int64_t ldb, int K, int64_t P, float lr, float momentum,
+                                 float wd, hipStream_t s);
+hipError_t grawa_launch_center_weights(const grawa_plan *p, const float *loss, float *beta_user,
+                                       int *leader_out, hipStream_t s);
 hipError_t grawa_launch_local_sgd(float *x, int64_t ldx, const void *g, int64_t ldg,
                                   grawa_dtype_t dt, int K, int64_t P, float lr, hipStream_t s);
 hipError_t grawa_launch_stream_copy(void *dst, const void *src, int64_t nbytes, hipStream_t s);

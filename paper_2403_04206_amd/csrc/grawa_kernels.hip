@@ -19,6 +19,8 @@
 //                      local SGD step x_k - lr g_k optionally applied on the way in
 //                                                   [display after eq. (2); Alg. 1, 2]
 //   k_local_sgd        x_k <- x_k - lr g_k                                 [Alg. 1, 2]
+//   k_nesterov         SGD with Nesterov momentum and weight decay         [App. B.2.2]
+//   k_center_weights   EASGD (uniform) and LSGD (leader) weights           [App. F]
 #include <hip/hip_ext.h>
 
 #include "grawa_internal.h"
@@ -436,6 +438,8 @@ __device__ __forceinline__ int layer_of(const int64_t *__restrict__ off, int lay
 // loads); < 0: the block contains a layer boundary, ~cell_layer[m] is the layer of its first
 // column and each lane finds its own layer.  Model-level weights pass cell_layer = nullptr.
 // The pull is x + lambda (c - x), one fma, which leaves a single worker exactly unchanged.
+// moving != 0 (EASGD, Appendix F): center_out holds the previous center c0 on entry and the
+// center used and stored is c0 + rho (c - c0).
 // WPE caps the waves per SIMD: the pass is fastest with roughly 32-48 row loads in flight per
 // SIMD (K x WPE); more only queues requests to K far-apart rows and costs DRAM efficiency
 // (measured: K = 16 at 3 waves 6.1 TB/s, at 8 waves 5.7; K = 8 at 4 waves 6.5, at 8 waves 6.2).
@@ -444,7 +448,7 @@ __global__ __launch_bounds__(GRAWA_CELL) __attribute__((amdgpu_waves_per_eu(1, W
     float *__restrict__ x, int64_t ldx, const GT *__restrict__ g, int64_t ldg, float lr,
     const float *__restrict__ beta, int64_t beta_stride, const int32_t *__restrict__ cell_layer,
     const int64_t *__restrict__ off, int L, int K, int64_t P, float lambda,
-    float *__restrict__ center_out)
+    float *__restrict__ center_out, float rho, int moving)
 {
     const int64_t cell0 = (int64_t)blockIdx.x * GRAWA_CELL; // wave-uniform
     const unsigned t = threadIdx.x;
@@ -468,6 +472,8 @@ __global__ __launch_bounds__(GRAWA_CELL) __attribute__((amdgpu_waves_per_eu(1, W
                     v[k] = fmaf(-lr, Grad<GT>::template lane<NT>(uniform_base(gb + (int64_t)k * ldg), goff), v[k]);
         }
     }
+    float cprev = 0.f;
+    if (moving && ok) cprev = ld_lane<NT, float>(uniform_base(center_out + cell0), xoff);
 
     const int info = cell_layer ? cell_layer[blockIdx.x] : 0;
     float c = 0.f;
@@ -482,6 +488,7 @@ __global__ __launch_bounds__(GRAWA_CELL) __attribute__((amdgpu_waves_per_eu(1, W
         for (int k = 0; k < KT; ++k)
             if (k < nk) c = fmaf(b[(int64_t)k * beta_stride], v[k], c);
     }
+    if (moving) c = fmaf(rho, c - cprev, cprev);
 
     if (ok) {
 #pragma unroll
@@ -499,7 +506,7 @@ __global__ __launch_bounds__(GRAWA_CELL) void k_center_pull_any(
     float *__restrict__ x, int64_t ldx, const GT *__restrict__ g, int64_t ldg, float lr,
     const float *__restrict__ beta, int64_t beta_stride, const int32_t *__restrict__ cell_layer,
     const int64_t *__restrict__ off, int L, int K, int64_t P, float lambda,
-    float *__restrict__ center_out)
+    float *__restrict__ center_out, float rho, int moving)
 {
     const int64_t i = (int64_t)blockIdx.x * GRAWA_CELL + threadIdx.x;
     if (i >= P) return;
@@ -515,6 +522,7 @@ __global__ __launch_bounds__(GRAWA_CELL) void k_center_pull_any(
         if (SGD) v = fmaf(-lr, Grad<GT>::one(g + (int64_t)k * ldg + i), v);
         c = fmaf(b[(int64_t)k * beta_stride], v, c);
     }
+    if (moving) c = fmaf(rho, c - center_out[i], center_out[i]);
     for (int k = 0; k < K; ++k) {
         float v = x[(int64_t)k * ldx + i];
         if (SGD) v = fmaf(-lr, Grad<GT>::one(g + (int64_t)k * ldg + i), v);
@@ -609,6 +617,91 @@ __global__ __launch_bounds__(GRAWA_CELL) void k_local_sgd(float *__restrict__ x,
     if (blockIdx.x == 0 && threadIdx.x < (unsigned)(P - nvec * V)) {
         const int64_t i = nvec * V + threadIdx.x;
         xr[i] = fmaf(-lr, Grad<GT>::one(gr + i), xr[i]);
+    }
+}
+
+// grid and lane layout of k_local_sgd.  One step of SGD with Nesterov momentum and weight decay
+// (the local optimizer of Appendix B.2.2), buf = momentum buffer [K][ldb], zero before the first step:
+//     d = g + wd x ;  buf <- momentum buf + d ;  x <- x - lr (d + momentum buf).
+template <typename GT, int V, bool NT>
+__global__ __launch_bounds__(GRAWA_CELL) void k_nesterov(float *__restrict__ x, int64_t ldx,
+                                                         const GT *__restrict__ g, int64_t ldg,
+                                                         float *__restrict__ buf, int64_t ldb, int64_t P,
+                                                         float lr, float momentum, float wd)
+{
+    typedef typename FloatVec<V>::T XV;
+    const int64_t nvec = P / V;
+    const int64_t j0 = (int64_t)blockIdx.x * (GRAWA_CELL * GRAWA_SGD_U) + threadIdx.x;
+    float *xr = x + (int64_t)blockIdx.y * ldx;
+    float *br = buf + (int64_t)blockIdx.y * ldb;
+    const GT *gr = g + (int64_t)blockIdx.y * ldg;
+    XV xv[GRAWA_SGD_U], bv[GRAWA_SGD_U];
+    float gf[GRAWA_SGD_U][V];
+#pragma unroll
+    for (int u = 0; u < GRAWA_SGD_U; ++u) {
+        const int64_t j = j0 + u * GRAWA_CELL;
+        if (j < nvec) {
+            const XV *xp = reinterpret_cast<const XV *>(xr + j * V);
+            const XV *bp = reinterpret_cast<const XV *>(br + j * V);
+            xv[u] = NT ? __builtin_nontemporal_load(xp) : *xp;
+            bv[u] = NT ? __builtin_nontemporal_load(bp) : *bp;
+            GradVec<GT, V, NT>::load(gr + j * V, gf[u]);
+        }
+    }
+    __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+    for (int u = 0; u < GRAWA_SGD_U; ++u) {
+        const int64_t j = j0 + u * GRAWA_CELL;
+        if (j < nvec) {
+            XV xo = xv[u], bo = bv[u];
+#pragma unroll
+            for (int c = 0; c < V; ++c) {
+                const float xc = vec_get<V>(xv[u], c);
+                const float d = fmaf(wd, xc, gf[u][c]);
+                const float b = fmaf(momentum, vec_get<V>(bv[u], c), d);
+                vec_set<V>(bo, c, b);
+                vec_set<V>(xo, c, fmaf(-lr, fmaf(momentum, b, d), xc));
+            }
+            XV *xp = reinterpret_cast<XV *>(xr + j * V);
+            XV *bp = reinterpret_cast<XV *>(br + j * V);
+            if (NT) {
+                __builtin_nontemporal_store(xo, xp);
+                __builtin_nontemporal_store(bo, bp);
+            } else {
+                *xp = xo;
+                *bp = bo;
+            }
+        }
+    }
+    if (blockIdx.x == 0 && threadIdx.x < (unsigned)(P - nvec * V)) {
+        const int64_t i = nvec * V + threadIdx.x;
+        const float xc = xr[i];
+        const float d = fmaf(wd, xc, Grad<GT>::one(gr + i));
+        const float b = fmaf(momentum, br[i], d);
+        br[i] = b;
+        xr[i] = fmaf(-lr, fmaf(momentum, b, d), xc);
+    }
+}
+
+// Weights of the competing centers of Appendix F, written where the pull kernel reads its
+// model-level weights.  loss == nullptr: EASGD, every worker 1/K.  Otherwise LSGD: weight 1 for
+// the worker with the smallest loss (the first one on ties), 0 for the rest; its index goes to
+// leader_out when given.  One thread: K is at most 1024.
+__global__ void k_center_weights(const float *__restrict__ loss, int K, float *__restrict__ beta,
+                                 float *__restrict__ beta_user, int *__restrict__ leader_out)
+{
+    if (blockIdx.x != 0 || threadIdx.x != 0) return;
+    int best = -1;
+    if (loss) {
+        best = 0;
+        for (int k = 1; k < K; ++k)
+            if (loss[k] < loss[best]) best = k;
+        if (leader_out) *leader_out = best;
+    }
+    for (int k = 0; k < K; ++k) {
+        const float b = loss ? (k == best ? 1.f : 0.f) : 1.f / (float)K;
+        beta[k] = b;
+        if (beta_user) beta_user[k] = b;
     }
 }
 
@@ -759,25 +852,25 @@ constexpr int grawa_waves_for(int k, bool sgd)
 
 template <int KT, bool EXACT, bool SGD, typename GT, bool NT>
 static void launch_cp(const grawa_plan *p, float *x, int64_t ldx, const void *g, int64_t ldg, float lr,
-                      const float *beta, int per_layer, float lambda, float *center_out, hipStream_t s,
-                      hipEvent_t e0, hipEvent_t e1)
+                      const float *beta, int per_layer, float lambda, float *center_out, float rho, int moving,
+                      hipStream_t s, hipEvent_t e0, hipEvent_t e1)
 {
     hipExtLaunchKernelGGL((k_center_pull<KT, EXACT, SGD, GT, NT, grawa_waves_for(KT, SGD)>),
                           dim3((unsigned)p->n_cells), dim3(GRAWA_CELL), 0, s, e0, e1, 0, x, ldx, (const GT *)g, ldg,
                           lr, beta, per_layer ? (int64_t)p->L : (int64_t)1,
                           per_layer ? (const int32_t *)p->d_cell_layer : (const int32_t *)nullptr,
-                          (const int64_t *)p->d_off, p->L, p->K, p->P, lambda, center_out);
+                          (const int64_t *)p->d_off, p->L, p->K, p->P, lambda, center_out, rho, moving);
 }
 
 // One kernel per worker count up to 32 (fully unrolled, no guards); 33..64 workers share a
 // guarded 64-slot kernel; beyond that the two-sweep kernel.
 template <bool SGD, typename GT, bool NT>
 static void dispatch_cp(const grawa_plan *p, float *x, int64_t ldx, const void *g, int64_t ldg, float lr,
-                        const float *beta, int per_layer, float lambda, float *center_out, hipStream_t s,
-                        hipEvent_t e0, hipEvent_t e1)
+                        const float *beta, int per_layer, float lambda, float *center_out, float rho, int moving,
+                        hipStream_t s, hipEvent_t e0, hipEvent_t e1)
 {
 #define GRAWA_CP_CASE(N) \
-    case N: launch_cp<N, true, SGD, GT, NT>(p, x, ldx, g, ldg, lr, beta, per_layer, lambda, center_out, s, e0, e1); break;
+    case N: launch_cp<N, true, SGD, GT, NT>(p, x, ldx, g, ldg, lr, beta, per_layer, lambda, center_out, rho, moving, s, e0, e1); break;
     const int K = p->K;
     switch (K) {
         GRAWA_CP_CASE(1) GRAWA_CP_CASE(2) GRAWA_CP_CASE(3) GRAWA_CP_CASE(4) GRAWA_CP_CASE(5) GRAWA_CP_CASE(6)
@@ -788,13 +881,13 @@ static void dispatch_cp(const grawa_plan *p, float *x, int64_t ldx, const void *
         GRAWA_CP_CASE(31) GRAWA_CP_CASE(32)
     default:
         if (K <= 64)
-            launch_cp<64, false, SGD, GT, NT>(p, x, ldx, g, ldg, lr, beta, per_layer, lambda, center_out, s, e0, e1);
+            launch_cp<64, false, SGD, GT, NT>(p, x, ldx, g, ldg, lr, beta, per_layer, lambda, center_out, rho, moving, s, e0, e1);
         else
             hipExtLaunchKernelGGL((k_center_pull_any<SGD, GT>), dim3((unsigned)p->n_cells), dim3(GRAWA_CELL), 0, s,
                                   e0, e1, 0, x, ldx, (const GT *)g, ldg, lr, beta,
                                   per_layer ? (int64_t)p->L : (int64_t)1,
                                   per_layer ? (const int32_t *)p->d_cell_layer : (const int32_t *)nullptr,
-                                  (const int64_t *)p->d_off, p->L, K, p->P, lambda, center_out);
+                                  (const int64_t *)p->d_off, p->L, K, p->P, lambda, center_out, rho, moving);
     }
 #undef GRAWA_CP_CASE
 }
@@ -810,22 +903,22 @@ static bool rows_line_aligned(const void *base, int64_t ld, int elem_bytes)
 
 hipError_t grawa_launch_center_pull(const grawa_plan *p, float *x, int64_t ldx, const float *beta,
                                     int per_layer, float lambda, const void *g_sgd, int64_t ldg_sgd,
-                                    grawa_dtype_t dt, float lr, int fuse_sgd, float *center_out,
-                                    hipStream_t s, hipEvent_t e0, hipEvent_t e1)
+                                    grawa_dtype_t dt, float lr, int fuse_sgd, float *center_out, float rho,
+                                    int moving, hipStream_t s, hipEvent_t e0, hipEvent_t e1)
 {
     // Streaming accesses pay off only when the arrays do not fit the last-level cache anyway.
     bool nt = (int64_t)p->K * p->P * 4 > GRAWA_STREAMING_MIN_BYTES && rows_line_aligned(x, ldx, 4) &&
               (!center_out || rows_line_aligned(center_out, 0, 4));
     if (fuse_sgd) nt = nt && rows_line_aligned(g_sgd, ldg_sgd, dt == GRAWA_BF16 ? 2 : 4);
     if (!fuse_sgd) {
-        if (nt) dispatch_cp<false, float, true>(p, x, ldx, nullptr, 0, 0.f, beta, per_layer, lambda, center_out, s, e0, e1);
-        else dispatch_cp<false, float, false>(p, x, ldx, nullptr, 0, 0.f, beta, per_layer, lambda, center_out, s, e0, e1);
+        if (nt) dispatch_cp<false, float, true>(p, x, ldx, nullptr, 0, 0.f, beta, per_layer, lambda, center_out, rho, moving, s, e0, e1);
+        else dispatch_cp<false, float, false>(p, x, ldx, nullptr, 0, 0.f, beta, per_layer, lambda, center_out, rho, moving, s, e0, e1);
     } else if (dt == GRAWA_BF16) {
-        if (nt) dispatch_cp<true, uint16_t, true>(p, x, ldx, g_sgd, ldg_sgd, lr, beta, per_layer, lambda, center_out, s, e0, e1);
-        else dispatch_cp<true, uint16_t, false>(p, x, ldx, g_sgd, ldg_sgd, lr, beta, per_layer, lambda, center_out, s, e0, e1);
+        if (nt) dispatch_cp<true, uint16_t, true>(p, x, ldx, g_sgd, ldg_sgd, lr, beta, per_layer, lambda, center_out, rho, moving, s, e0, e1);
+        else dispatch_cp<true, uint16_t, false>(p, x, ldx, g_sgd, ldg_sgd, lr, beta, per_layer, lambda, center_out, rho, moving, s, e0, e1);
     } else {
-        if (nt) dispatch_cp<true, float, true>(p, x, ldx, g_sgd, ldg_sgd, lr, beta, per_layer, lambda, center_out, s, e0, e1);
-        else dispatch_cp<true, float, false>(p, x, ldx, g_sgd, ldg_sgd, lr, beta, per_layer, lambda, center_out, s, e0, e1);
+        if (nt) dispatch_cp<true, float, true>(p, x, ldx, g_sgd, ldg_sgd, lr, beta, per_layer, lambda, center_out, rho, moving, s, e0, e1);
+        else dispatch_cp<true, float, false>(p, x, ldx, g_sgd, ldg_sgd, lr, beta, per_layer, lambda, center_out, rho, moving, s, e0, e1);
     }
     return hipGetLastError();
 }
@@ -846,6 +939,32 @@ hipError_t grawa_launch_local_sgd(float *x, int64_t ldx, const void *g, int64_t 
         if (nt) k_local_sgd<float, 1, true><<<grid, block, 0, s>>>(x, ldx, (const float *)g, ldg, P, lr);
         else k_local_sgd<float, 1, false><<<grid, block, 0, s>>>(x, ldx, (const float *)g, ldg, P, lr);
     }
+    return hipGetLastError();
+}
+
+hipError_t grawa_launch_nesterov(float *x, int64_t ldx, const void *g, int64_t ldg, grawa_dtype_t dt, float *buf,
+                                 int64_t ldb, int K, int64_t P, float lr, float momentum, float wd, hipStream_t s)
+{
+    const int64_t per_block = GRAWA_CELL * GRAWA_SGD_U * (dt == GRAWA_BF16 ? 4 : 1);
+    int64_t gx = (P + per_block - 1) / per_block;
+    if (gx < 1) gx = 1;
+    const dim3 grid((unsigned)gx, (unsigned)K), block(GRAWA_CELL);
+    const bool nt = (int64_t)K * P * 4 > GRAWA_STREAMING_MIN_BYTES && rows_line_aligned(x, ldx, 4) &&
+                    rows_line_aligned(buf, ldb, 4) && rows_line_aligned(g, ldg, dt == GRAWA_BF16 ? 2 : 4);
+    if (dt == GRAWA_BF16) {
+        if (nt) k_nesterov<uint16_t, 4, true><<<grid, block, 0, s>>>(x, ldx, (const uint16_t *)g, ldg, buf, ldb, P, lr, momentum, wd);
+        else k_nesterov<uint16_t, 4, false><<<grid, block, 0, s>>>(x, ldx, (const uint16_t *)g, ldg, buf, ldb, P, lr, momentum, wd);
+    } else {
+        if (nt) k_nesterov<float, 1, true><<<grid, block, 0, s>>>(x, ldx, (const float *)g, ldg, buf, ldb, P, lr, momentum, wd);
+        else k_nesterov<float, 1, false><<<grid, block, 0, s>>>(x, ldx, (const float *)g, ldg, buf, ldb, P, lr, momentum, wd);
+    }
+    return hipGetLastError();
+}
+
+hipError_t grawa_launch_center_weights(const grawa_plan *p, const float *loss, float *beta_user, int *leader_out,
+                                       hipStream_t s)
+{
+    k_center_weights<<<dim3(1), dim3(GRAWA_WAVE), 0, s>>>(loss, p->K, p->d_beta_model, beta_user, leader_out);
     return hipGetLastError();
 }
 

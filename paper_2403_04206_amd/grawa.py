@@ -61,6 +61,9 @@ def lib():
         "grawa_local_lgrawa_update": (it, [vp, vp, i64, fl, vp, vp, vp, vp]),
         "grawa_local_mgrawa_update": (it, [vp, vp, i64, fl, vp, vp, vp, vp]),
         "grawa_local_scores_reset": (it, [vp, vp]),
+        "grawa_local_nesterov": (it, [vp, i64, vp, i64, it, vp, i64, it, i64, fl, fl, fl, vp]),
+        "grawa_easgd_update": (it, [vp, vp, i64, fl, fl, vp, vp]),
+        "grawa_lsgd_update": (it, [vp, vp, i64, vp, fl, vp, vp, vp]),
         "grawa_plan_profile": (it, [vp, it]),
         "grawa_plan_profile_read": (it, [vp, C.POINTER(it), C.POINTER(dbl), C.POINTER(dbl)]),
         "grawa_stream_copy": (it, [vp, vp, i64, vp]),
@@ -222,6 +225,17 @@ class Plan:
     def local_scores_reset(self, stream=None):
         _check(lib().grawa_local_scores_reset(self._h, _stream(stream)), "grawa_local_scores_reset")
 
+    # -- competing centers (Appendix F) ---------------------------------------------
+    def easgd_update(self, x, lam, rho, center, stream=None):
+        xp, ldx = _params(x)
+        _check(lib().grawa_easgd_update(self._h, xp, ldx, float(lam), float(rho), _ptr(center), _stream(stream)),
+               "grawa_easgd_update")
+
+    def lsgd_update(self, x, losses, lam, center_out=None, leader_out=None, stream=None):
+        xp, ldx = _params(x)
+        _check(lib().grawa_lsgd_update(self._h, xp, ldx, _ptr(losses), float(lam), _ptr(center_out),
+                                       _ptr(leader_out), _stream(stream)), "grawa_lsgd_update")
+
     # -- measurement aid ------------------------------------------------------------
     def profile(self, enable: bool):
         _check(lib().grawa_plan_profile(self._h, 1 if enable else 0), "grawa_plan_profile")
@@ -249,6 +263,17 @@ def local_sgd_prox(x, g, lr, center, mu, tau, P=None, stream=None):
     P = x.shape[1] if P is None else int(P)
     _check(lib().grawa_local_sgd_prox(xp, ldx, gp, ldg, dt, K, P, float(lr), _ptr(center), float(mu), float(tau),
                                       _stream(stream)), "grawa_local_sgd_prox")
+
+
+def local_nesterov(x, g, buf, lr, momentum, weight_decay=0.0, P=None, stream=None):
+    """grawa_local_nesterov: one Nesterov-momentum SGD step with weight decay; buf is updated in place."""
+    xp, ldx = _params(x)
+    bp, ldb = _params(buf)
+    gp, ldg, dt = _grads(g)
+    K = x.shape[0]
+    P = x.shape[1] if P is None else int(P)
+    _check(lib().grawa_local_nesterov(xp, ldx, gp, ldg, dt, bp, ldb, K, P, float(lr), float(momentum),
+                                      float(weight_decay), _stream(stream)), "grawa_local_nesterov")
 
 
 def stream_copy(dst, src, stream=None):
