@@ -13,7 +13,8 @@ fused) divided by the measured time per step.  `roofline` is the same kind of fi
 dominant kernel alone (center+pull), from HIP start/stop events attached to that kernel's
 launches while the timed steps are repeated once more (so that `value` carries no event
 overhead).  `cpu_baseline` is the float64 CPU reference timed on a bounded sample of the
-same workload on this machine's host cores.
+same workload on this machine's host cores.  `phases` times the calls around the distributed
+phase (local steps, Local-GRAWA round, Nesterov step, EASGD / LSGD) on the same workload.
 """
 import argparse
 import json
@@ -38,6 +39,9 @@ def parse():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-sweep", action="store_true", help="do not also time the other configurations")
     ap.add_argument("--cpu-seconds", type=float, default=15.0, help="target CPU time of the reference sample")
+    ap.add_argument("--no-phases", action="store_true", help="do not also time the local-phase and Appendix F calls")
+    ap.add_argument("--only-phases", action="store_true",
+                    help="time only the local-phase and Appendix F calls on --config (for kernel profiles)")
     return ap.parse_args()
 
 
@@ -124,6 +128,59 @@ def copy_ceiling(torch, grawa, nbytes=1 << 31, reps=10):
     return {"GBps": 2 * nbytes / (ms * 1e-3) / 1e9, "ms": ms, "bytes_moved": 2 * nbytes, "verified": ok}
 
 
+def time_phases(torch, grawa, W, idx, steps, warmup):
+    """The calls around the distributed phase, on the same workload: local steps of Algorithms 1 and 2
+    (SGD, + proximity step, + the running norm estimate of Appendix G), the local optimizer of the
+    experiments (Nesterov momentum, Appendix B.2.2), one Local-GRAWA round, and the EASGD / LSGD
+    phases of Appendix F.  GB/s under each call's minimum-traffic byte model, from events on the
+    stream the kernels are launched on (torch's current stream)."""
+    w = W.config(idx)
+    x, g = W.make_inputs(w, device="cuda:0")
+    K, P, sg = w.K, w.P, w.grad_bytes
+    xv, gv = x[:, :P], g[:, :P]
+    cen = torch.zeros(W.round_up(P, 256), device="cuda:0")
+    losses = torch.rand(K, device="cuda:0", generator=torch.Generator(device="cuda:0").manual_seed(1))
+    lr = 1e-3
+    out = {}
+
+    def run(name, nbytes, fn):
+        for _ in range(warmup):
+            fn()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        torch.cuda.synchronize()
+        e0.record()
+        for _ in range(steps):
+            fn()
+        e1.record()
+        torch.cuda.synchronize()
+        ms = e0.elapsed_time(e1) / steps
+        out[name] = {"ms": ms, "bytes": nbytes, "GBps": nbytes / (ms * 1e-3) / 1e9,
+                     "frac_of_peak": nbytes / (ms * 1e-3) / 1e9 / HBM_PEAK_GBPS}
+
+    step = K * P * (8 + sg)
+    with grawa.Plan(K, P, w.offsets) as plan:
+        def local_round():
+            plan.local_step_scored(xv, gv, lr, 0.9)
+            plan.local_lgrawa_update(xv, w.lam)
+
+        run("local_sgd", step, lambda: grawa.local_sgd(xv, gv, lr))
+        if K <= 64:
+            run("local_sgd_prox", step + 4 * P, lambda: grawa.local_sgd_prox(xv, gv, lr, cen, 0.05, 16.0))
+            run("local_step_scored", step, lambda: plan.local_step_scored(xv, gv, lr, 0.9))
+            run("local_step_scored_prox", step + 4 * P,
+                lambda: plan.local_step_scored(xv, gv, lr, 0.9, center=cen, mu=0.05, tau=16.0))
+            plan.local_scores_reset()
+            run("local_round_1step_lgrawa", step + K * P * 8, local_round)
+        run("easgd_update", K * P * 8 + 8 * P, lambda: plan.easgd_update(xv, w.lam, 0.5, cen))
+        run("lsgd_update", K * P * 8, lambda: plan.lsgd_update(xv, losses, w.lam))
+    del cen
+    buf = torch.zeros_like(x)
+    run("local_nesterov", K * P * (16 + sg), lambda: grawa.local_nesterov(xv, gv, buf[:, :P], lr, 0.9, 5e-4))
+    del buf, x, g
+    torch.cuda.empty_cache()
+    return {"workload": w.name, "steps": steps, "calls": out}
+
+
 def cpu_baseline(torch, W, w, variant, target_seconds):
     """The float64 CPU reference, as it stands, on the first n columns of the same seeded
     workload (all K workers, layers clipped to the sample); n is chosen from a short trial so
@@ -149,16 +206,20 @@ def cpu_baseline(torch, W, w, variant, target_seconds):
     t = run(n)
     n_full = int(min(w.P, n * target_seconds / max(t, 1e-6)))
     n_full -= n_full % 8
+    reps = 1
     if n_full > n:
         n, t = n_full, run(n_full)
+        if n == w.P - w.P % 8 and t < 0.6 * target_seconds:      # the whole workload is short: repeat it
+            reps = int(min(50, max(1, round(target_seconds / t)) ))
+            t = sum(run(n) for _ in range(reps)) / reps
     del x_dev, g_dev
     per = w.grad_bytes + 8 + (w.grad_bytes if w.fused_sgd else 0)
     sample_bytes = w.K * n * per
     return {
         "value": sample_bytes / t / 1e9, "unit": "GB/s", "cores": 1, "kind": "oracle",
-        "sample": "first %d of %d columns of %s, all %d workers, layers clipped to the sample; %.1f s of CPU "
-                  "time; same byte model as value" % (n, w.P, w.name, w.K, t),
-        "seconds": t, "updates_per_s_extrapolated": 1.0 / (t * w.P / n), "host_cores_available": os.cpu_count(),
+        "sample": "first %d of %d columns of %s, all %d workers, layers clipped to the sample, %d update(s); "
+                  "%.1f s of CPU time in the reference; same byte model as value" % (n, w.P, w.name, w.K, reps, t * reps),
+        "seconds": t * reps, "updates_per_s_extrapolated": 1.0 / (t * w.P / n), "host_cores_available": os.cpu_count(),
     }
 
 
@@ -196,6 +257,11 @@ def main():
     if not os.path.exists(grawa.LIB_PATH):
         buildlib.build(force=True)
 
+    if a.only_phases:
+        print(json.dumps({"metric": "grawa_phase_calls_hbm_bandwidth", "unit": "GB/s", "n_gpus": 1, "steps": a.steps,
+                          "warmup": a.warmup, "data": "synthetic", "dtype": "f32",
+                          "phases": time_phases(torch, grawa, W, a.config, a.steps, a.warmup)}), flush=True)
+        return
     stats, x, g, w = time_config(torch, grawa, W, a.config, a.variant, a.steps, a.warmup)
     del x, g
     torch.cuda.empty_cache()
@@ -235,6 +301,8 @@ def main():
                 sweep.append({k: s[k] for k in ("workload", "variant", "ms_per_step", "updates_per_s", "GBps",
                                                  "frac_of_peak", "pull_kernel_GBps", "norm_kernel_GBps")})
         out["all_configs"] = sweep
+    if not a.no_phases and not a.no_sweep:
+        out["phases"] = time_phases(torch, grawa, W, a.config, a.steps, a.warmup)
     if not a.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(torch, W, w, variant, a.cpu_seconds)
     print(json.dumps(out), flush=True)

@@ -6,6 +6,8 @@ Expected input, one directory per run (any parent folder):
                                     -- python3 bench.py --config <N> --no-sweep --no-cpu-baseline
     <dir>/prof_cfg<N>_fetch   same command with  --pmc FETCH_SIZE   instead of --kernel-trace --stats
     <dir>/prof_cfg<N>_write   same command with  --pmc WRITE_SIZE
+    <dir>/prof_cfg<N>_phases  (optional) --kernel-trace --stats of
+                                    python3 bench.py --config <N> --only-phases
 
 FETCH_SIZE / WRITE_SIZE are reported in KiB per dispatch.  Each is scaled by what the same
 counter reads, in the same run, for the library's plain copy kernel (bench.py launches it over
@@ -148,6 +150,64 @@ def summarize(base: str, cfg: int, out_dir: str):
     return w["workload"], {"variant": w["variant"], "fetch_scale": f_scale, "write_scale": w_scale, "kernels": traffic}
 
 
+def template_args(name: str):
+    if "<" not in name:
+        return []
+    return [a.strip() for a in name[name.index("<") + 1:name.rindex(">")].split(",")]
+
+
+def summarize_phases(base: str, cfg: int, out_dir: str):
+    """Kernel table of the calls around the distributed phase (bench.py --only-phases)."""
+    run_dir = os.path.join(base, "prof_cfg%d_phases" % cfg)
+    if not os.path.isdir(run_dir):
+        return None
+    stats = read_stats(run_dir)
+    bl = bench_line(run_dir)
+    ph = bl["phases"]
+    from . import workloads as W
+    w = W.config(cfg)
+    K, P, gb = w.K, w.P, w.grad_bytes
+    lines = ["# rocprofv3 summary: local-phase, Nesterov and Appendix F kernels, %s" % ph["workload"], "",
+             "K=%d workers, L=%d layers, P=%d parameters, gradients %s, library source hash %s." %
+             (K, w.L, P, w.grad_dtype, kernel_source_hash()), "",
+             "Command (run from /tmp with TMPDIR=/tmp, repository root = $R):", "",
+             "    rocprofv3 --kernel-trace --stats -d <out> --output-format csv -- python3 $R/bench.py --config %d "
+             "--only-phases" % cfg, "",
+             "## Calls, from stream events inside bench.py (minimum-traffic byte model of each call)", "",
+             "| call | ms | bytes | GB/s | % of 8 TB/s |", "|---|---|---|---|---|"]
+    for name, c in ph["calls"].items():
+        lines.append("| %s | %.4f | %d | %.0f | %.1f |" % (name, c["ms"], c["bytes"], c["GBps"], 100 * c["frac_of_peak"]))
+    lines += ["", "## --kernel-trace --stats (library kernels only)", "",
+              "k_rows_step<K, exact, grad type, streaming, PROX, SCORE, waves>: SGD (+ proximity step) (+ per-tile "
+              "gradient sums of squares).  k_center_pull here serves the Local-GRAWA communication and the EASGD and "
+              "LSGD phases together.", "",
+              "| kernel | calls | avg us | min us | max us | algorithmic bytes/launch | GB/s at avg | % of 8 TB/s |",
+              "|---|---|---|---|---|---|---|---|"]
+    for name, calls, avg, mn, mx, _pct in stats:
+        base_name = name.split("<")[0]
+        if not base_name.startswith("k_"):
+            continue
+        ta = template_args(name)
+        ab = None
+        if base_name == "k_local_sgd":
+            ab = K * P * (8 + gb)
+        elif base_name == "k_nesterov":
+            ab = K * P * (16 + gb)
+        elif base_name == "k_rows_step":
+            ab = K * P * (8 + gb) + (4 * P if len(ta) > 4 and ta[4] == "true" else 0)
+        elif base_name == "k_center_pull":
+            ab = K * P * 8
+        gbps = "%.0f" % (ab / avg) if ab else "-"
+        frac = "%.1f" % (100 * ab / avg / 8000.0) if ab else "-"
+        lines.append("| %s | %d | %.1f | %.1f | %.1f | %s | %s | %s |" %
+                     (name, calls, avg / 1e3, mn / 1e3, mx / 1e3, ab if ab else "-", gbps, frac))
+    lines.append("")
+    out = os.path.join(out_dir, "phase_kernels_%s.md" % ph["workload"])
+    with open(out, "w") as f:
+        f.write("\n".join(lines) + "\n")
+    return out
+
+
 def main(argv):
     base = argv[1]
     cfgs = [int(a) for a in argv[2:]] or [2, 3, 4]
@@ -158,6 +218,8 @@ def main(argv):
         name, t = summarize(base, c, out_dir)
         tj["workloads"][name] = t
         print("wrote summary for", name)
+        if summarize_phases(base, c, out_dir):
+            print("wrote phase summary for", name)
     with open(os.path.join(out_dir, "traffic.json"), "w") as f:
         json.dump(tj, f, indent=1)
 
