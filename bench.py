@@ -65,6 +65,14 @@ def call_update(plan, w, x, g, variant):
             plan.mgrawa_update(x[:, :P], g[:, :P], w.lam)
 
 
+def spread(v):
+    v = sorted(v)
+    if not v:
+        return None
+    return {"min": v[0], "median": v[len(v) // 2] if len(v) % 2 else 0.5 * (v[len(v) // 2 - 1] + v[len(v) // 2]),
+            "mean": sum(v) / len(v), "max": v[-1], "n": len(v)}
+
+
 def time_config(torch, grawa, W, idx, variant, steps, warmup):
     """Returns (stats dict, x, g, w) with x, g left on the device (x has been updated)."""
     w = W.config(idx)
@@ -89,6 +97,7 @@ def time_config(torch, grawa, W, idx, variant, steps, warmup):
             call_update(plan, w, x, g, variant)
         torch.cuda.synchronize()
         prof = plan.profile_read()
+        per_call = [plan.profile_read_call(i) for i in range(prof["calls"])]
         plan.profile(False)
     ms = (t1 - t0) * 1e3 / steps
     model_bytes = w.update_bytes()
@@ -105,6 +114,9 @@ def time_config(torch, grawa, W, idx, variant, steps, warmup):
         "norm_kernel_ms": norm_ms, "norm_kernel_GBps": norm_bytes / (norm_ms * 1e-3) / 1e9 if norm_ms > 0 else None,
         "pull_kernel_ms": pull_ms, "pull_kernel_GBps": pull_bytes / (pull_ms * 1e-3) / 1e9 if pull_ms > 0 else None,
         "pull_kernel_bytes": pull_bytes, "tile_elems": info["tile_elems"], "n_tiles": info["n_tiles"],
+        # per update, first kernel start to last kernel end on the device (the event pass)
+        "device_ms": spread([c["span_ms"] for c in per_call]),
+        "pull_kernel_ms_spread": spread([c["pull_ms"] for c in per_call]),
     }
     del x0
     return stats, x, g, w
@@ -272,6 +284,7 @@ def main():
         "unit": "GB/s", "frac": (stats["pull_kernel_GBps"] or 0.0) / HBM_PEAK_GBPS,
         "traffic": measured_traffic(w.name, stats["variant"]),
         "bytes_per_launch": stats["pull_kernel_bytes"], "avg_launch_ms": stats["pull_kernel_ms"],
+        "launch_ms": stats["pull_kernel_ms_spread"],
         "norm_kernel": {"achieved": stats["norm_kernel_GBps"], "avg_launch_ms": stats["norm_kernel_ms"],
                         "frac": (stats["norm_kernel_GBps"] or 0.0) / HBM_PEAK_GBPS},
     }
@@ -283,7 +296,7 @@ def main():
                    "grad_dtype": w.grad_dtype, "lambda": w.lam, "bytes_per_update": stats["model_bytes"],
                    "tile_elems": stats["tile_elems"]},
         "frac_of_hbm_peak": stats["frac_of_peak"], "updates_per_s": stats["updates_per_s"],
-        "roofline": roofline,
+        "device_ms_per_update": stats["device_ms"], "roofline": roofline,
     }
     out["copy_kernel"] = copy_ceiling(torch, grawa)
     torch.cuda.empty_cache()

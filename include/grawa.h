@@ -179,7 +179,7 @@ grawa_status_t grawa_local_sgd_prox(float *x, int64_t ldx, const void *g, int64_
  *   t <- t + 1 ;  g_mvg <- gamma g_mvg + (1 - gamma) g_cur          (kept in the plan, fp64)
  *   x_k <- x_k - lr g_k ;  if center != NULL: x_k <- (1 - mu/tau) x_k + (mu/tau) center
  * 0 < gamma < 1, and gamma must not change between two communications
- * (INVALID_ARG).  K <= 64.
+ * (INVALID_ARG).  With a center K <= 64 (UNSUPPORTED beyond); without, any K of the plan.
  *
  * grawa_local_lgrawa_update / grawa_local_mgrawa_update: the communication step:
  *   g_est = gamma g_mvg / (1 - gamma^t)            (as printed, leading gamma included)
@@ -254,6 +254,11 @@ grawa_status_t grawa_lsgd_update(grawa_plan_t *plan, float *x, int64_t ldx, cons
  * Returns the number of recorded calls in *n_calls and the summed durations in
  * milliseconds of the two kernels (host pointers; any may be NULL).
  *
+ * grawa_plan_profile_read_call: the same for recorded call i alone
+ * (0 <= i < n_calls, else INVALID_ARG), plus in *span_ms the time from the start
+ * of its gradient-norm kernel to the end of its center+pull kernel, i.e. the
+ * whole update on the device (for a call without a norm pass: the pull alone).
+ *
  * grawa_stream_copy: dst[i] = src[i] for nbytes bytes (multiple of 16, both
  * pointers 16-byte aligned) with the same 128-bit access pattern as the update
  * kernels; a plain copy of known size used to calibrate hardware counters and
@@ -262,6 +267,8 @@ grawa_status_t grawa_lsgd_update(grawa_plan_t *plan, float *x, int64_t ldx, cons
 grawa_status_t grawa_plan_profile(grawa_plan_t *plan, int enable);
 grawa_status_t grawa_plan_profile_read(grawa_plan_t *plan, int *n_calls, double *norm_ms,
                                        double *pull_ms);
+grawa_status_t grawa_plan_profile_read_call(grawa_plan_t *plan, int i, double *norm_ms, double *pull_ms,
+                                            double *span_ms);
 grawa_status_t grawa_stream_copy(void *dst, const void *src, int64_t nbytes, void *stream);
 
 /* Number of tiles the plan cut the flat vector into, and the tile length in

@@ -190,6 +190,17 @@ grawa_status_t grawa_plan_create(grawa_plan_t **out, int K, int64_t P, int L,
     cut(TR, rtiles, layer_rtile0);
     const int64_t nt = (int64_t)tiles.size();
     const int64_t nrt = (int64_t)rtiles.size();
+    // Short tiles never cross a multiple of TR: index them by aligned block.
+    const int64_t nrb = (P + TR - 1) / TR;
+    std::vector<int32_t> block_rtile0((size_t)nrb + 1);
+    {
+        int64_t r = 0;
+        for (int64_t m = 0; m < nrb; ++m) {
+            block_rtile0[(size_t)m] = (int32_t)r;
+            while (r < nrt && rtiles[(size_t)r].start < (m + 1) * TR) ++r;
+        }
+        block_rtile0[(size_t)nrb] = (int32_t)nrt;
+    }
 
     // Cell map of the center+pull pass: block m covers columns [256 m, 256 m + 256).
     const int64_t cell = 256;
@@ -226,13 +237,14 @@ grawa_status_t grawa_plan_create(grawa_plan_t **out, int K, int64_t P, int L,
     const size_t b_tiles = round256(sizeof(GrawaTile) * (size_t)nt);
     const size_t b_rtiles = round256(sizeof(GrawaTile) * (size_t)nrt);
     const size_t b_lt0 = round256(sizeof(int32_t) * ((size_t)L + 1));
+    const size_t b_brt0 = round256(sizeof(int32_t) * ((size_t)nrb + 1));
     const size_t b_part = round256(sizeof(double) * (size_t)K * (size_t)(nrt > nt ? nrt : nt));
     const size_t b_S = round256(sizeof(double) * (size_t)K * (size_t)L);
     const size_t b_A = round256(sizeof(float) * (size_t)K * (size_t)L);
     const size_t b_bl = b_A;
     const size_t b_bm = round256(sizeof(float) * (size_t)K);
     const size_t b_mvg = b_S;
-    p->ws_bytes = b_off + b_cells + b_tiles + b_lt0 + b_rtiles + b_lt0 + b_part + b_S + b_A + b_bl + b_bm + b_mvg;
+    p->ws_bytes = b_off + b_cells + b_tiles + b_lt0 + b_rtiles + b_lt0 + b_brt0 + b_part + b_S + b_A + b_bl + b_bm + b_mvg;
     if (hipMalloc(&p->ws, p->ws_bytes) != hipSuccess) {
         (void)hipGetLastError();
         delete p;
@@ -245,6 +257,7 @@ grawa_status_t grawa_plan_create(grawa_plan_t **out, int K, int64_t P, int L,
     p->d_layer_tile0 = reinterpret_cast<int32_t *>(w); w += b_lt0;
     p->d_rtiles = reinterpret_cast<GrawaTile *>(w); w += b_rtiles;
     p->d_layer_rtile0 = reinterpret_cast<int32_t *>(w); w += b_lt0;
+    p->d_block_rtile0 = reinterpret_cast<int32_t *>(w); w += b_brt0;
     p->d_partials = reinterpret_cast<double *>(w); w += b_part;
     p->d_S = reinterpret_cast<double *>(w); w += b_S;
     p->d_A = reinterpret_cast<float *>(w); w += b_A;
@@ -258,6 +271,7 @@ grawa_status_t grawa_plan_create(grawa_plan_t **out, int K, int64_t P, int L,
         hipMemcpy(p->d_layer_tile0, layer_tile0.data(), sizeof(int32_t) * ((size_t)L + 1), hipMemcpyHostToDevice) != hipSuccess ||
         hipMemcpy(p->d_rtiles, rtiles.data(), sizeof(GrawaTile) * (size_t)nrt, hipMemcpyHostToDevice) != hipSuccess ||
         hipMemcpy(p->d_layer_rtile0, layer_rtile0.data(), sizeof(int32_t) * ((size_t)L + 1), hipMemcpyHostToDevice) != hipSuccess ||
+        hipMemcpy(p->d_block_rtile0, block_rtile0.data(), sizeof(int32_t) * ((size_t)nrb + 1), hipMemcpyHostToDevice) != hipSuccess ||
         hipMemset(p->d_partials, 0, b_part + b_S + b_A + b_bl + b_bm + b_mvg) != hipSuccess) {
         (void)hipFree(p->ws);
         delete p;
@@ -445,7 +459,7 @@ grawa_status_t grawa_local_step_scored(grawa_plan_t *p, float *x, int64_t ldx, c
     grawa_status_t st;
     if ((st = check_params(p, x, ldx)) != GRAWA_OK) return st;
     if ((st = check_grads(p->P, g, ldg, dt)) != GRAWA_OK) return st;
-    if (p->K > 64) return GRAWA_ERR_UNSUPPORTED;
+    if (center ? p->K > 64 : p->K > 65535) return GRAWA_ERR_UNSUPPORTED;
     if (!std::isfinite(lr) || !(gamma > 0.f) || !(gamma < 1.f)) return GRAWA_ERR_INVALID_ARG;
     if (p->local_t > 0 && (double)gamma != p->local_gamma) return GRAWA_ERR_INVALID_ARG; /* one gamma per round */
     float w = 0.f;
@@ -458,8 +472,12 @@ grawa_status_t grawa_local_step_scored(grawa_plan_t *p, float *x, int64_t ldx, c
     DeviceGuard guard(p->device);
     if (!guard.ok) return GRAWA_ERR_HIP;
     hipStream_t s = static_cast<hipStream_t>(stream);
-    GRAWA_TRY_HIP(grawa_launch_rows_step(x, ldx, g, ldg, dt, lr, center, w, p->d_rtiles, 1024, p->n_rtiles,
-                                         p->K, p->P, p->d_partials, s));
+    if (center) /* all K rows of a tile in one block: the stored center is read once */
+        GRAWA_TRY_HIP(grawa_launch_rows_step(x, ldx, g, ldg, dt, lr, center, w, p->d_rtiles, 1024, p->n_rtiles,
+                                             p->K, p->P, p->d_partials, s));
+    else /* row by row: the faster shape when nothing is shared between the rows */
+        GRAWA_TRY_HIP(grawa_launch_row_step_scored(x, ldx, g, ldg, dt, lr, p->d_rtiles, p->d_block_rtile0,
+                                                   p->n_rtiles, p->K, p->P, p->d_partials, s));
     GRAWA_TRY_HIP(grawa_launch_finalize_layers(p, nullptr, nullptr, s, 1, (double)gamma));
     p->local_t += 1;
     p->local_gamma = (double)gamma;
@@ -550,6 +568,22 @@ grawa_status_t grawa_plan_profile_read(grawa_plan_t *p, int *n_calls, double *no
     if (n_calls) *n_calls = p->profile_n;
     if (norm_ms) *norm_ms = a;
     if (pull_ms) *pull_ms = b;
+    return GRAWA_OK;
+}
+
+grawa_status_t grawa_plan_profile_read_call(grawa_plan_t *p, int i, double *norm_ms, double *pull_ms, double *span_ms)
+{
+    if (!p || i < 0 || i >= p->profile_n) return GRAWA_ERR_INVALID_ARG;
+    float a = 0.f, b = 0.f, c = 0.f;
+    GRAWA_TRY_HIP(hipEventElapsedTime(&b, p->ev[4 * i + 2], p->ev[4 * i + 3]));
+    c = b;
+    if (!p->profile_pull_only) {
+        GRAWA_TRY_HIP(hipEventElapsedTime(&a, p->ev[4 * i + 0], p->ev[4 * i + 1]));
+        GRAWA_TRY_HIP(hipEventElapsedTime(&c, p->ev[4 * i + 0], p->ev[4 * i + 3]));
+    }
+    if (norm_ms) *norm_ms = a;
+    if (pull_ms) *pull_ms = b;
+    if (span_ms) *span_ms = c;
     return GRAWA_OK;
 }
 

@@ -34,6 +34,7 @@ struct grawa_plan {
     int32_t *d_layer_tile0; // [L+1] first tile of every layer
     GrawaTile *d_rtiles;    // [n_rtiles] short tiles (1024 columns) of the scored local step
     int32_t *d_layer_rtile0; // [L+1]
+    int32_t *d_block_rtile0; // [ceil(P/1024)+1] first short tile of every aligned block of 1024 columns
     int64_t n_rtiles;
     int32_t *d_cell_layer;  // [n_cells] layer of a 256-column cell, or ~(first layer) if it holds a boundary
     double *d_partials;     // [K][n_tiles] per-tile sums of squares
@@ -73,6 +74,9 @@ hipError_t grawa_launch_center_pull(const grawa_plan *p, float *x, int64_t ldx, 
 hipError_t grawa_launch_nesterov(float *x, int64_t ldx, const void *g, int64_t ldg, grawa_dtype_t dt,
                                  float *buf, int64_t ldb, int K, int64_t P, float lr, float momentum,
                                  float wd, hipStream_t s);
+hipError_t grawa_launch_row_step_scored(float *x, int64_t ldx, const void *g, int64_t ldg, grawa_dtype_t dt,
+                                        float lr, const GrawaTile *tiles, const int32_t *block_tile0,
+                                        int64_t n_tiles, int K, int64_t P, double *partials, hipStream_t s);
 hipError_t grawa_launch_center_weights(const grawa_plan *p, const float *loss, float *beta_user,
                                        int *leader_out, hipStream_t s);
 hipError_t grawa_launch_local_sgd(float *x, int64_t ldx, const void *g, int64_t ldg,

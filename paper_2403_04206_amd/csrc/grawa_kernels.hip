@@ -535,7 +535,13 @@ __global__ __launch_bounds__(GRAWA_CELL) void k_center_pull_any(
 // local SGD step
 // ---------------------------------------------------------------------------------
 
-#define GRAWA_SGD_U 4 // vectors per lane of the plain SGD step (8 loads in flight per lane)
+// Vector shape of the per-row local steps: a lane handles U vectors of V adjacent columns.  fp32
+// gradients: V = 1, U = 4; bf16: V = 2, U = 2 (measured: 6.6-6.7 TB/s for both; bf16 at V = 4, U = 4
+// 5.7, at V = 1 4.5; more bytes in flight per lane cost bandwidth at full occupancy).
+#define GRAWA_SGD_V_F32 1
+#define GRAWA_SGD_U_F32 4
+#define GRAWA_SGD_V_BF16 2
+#define GRAWA_SGD_U_BF16 2
 
 // V gradient elements (V * sizeof(GT) = 4 or 8 bytes, naturally aligned) widened to float.
 template <typename GT, int V, bool NT> struct GradVec;
@@ -575,25 +581,23 @@ template <int V> __device__ __forceinline__ void vec_set(typename FloatVec<V>::T
     else v[c] = f;
 }
 
-// grid (ceil(P / (256*4*V)), K), block 256.  x[k][i] -= lr * g[k][i].  A lane handles 4 vectors of
-// V adjacent columns, vectors of a block 256*V columns apart; V = 1 for fp32 gradients (4-byte
-// accesses measured fastest for this read-modify-write stream) and 4 for bf16 (an 8-byte gradient
-// load with a 16-byte parameter access).  Rows start 16-byte aligned, so every vector is
-// naturally aligned; the last P % V columns of a row take a scalar path.
-template <typename GT, int V, bool NT>
+// grid (ceil(P / (256*U*V)), K), block 256.  x[k][i] -= lr * g[k][i].  A lane handles U vectors of
+// V adjacent columns, vectors of a block 256*V columns apart.  Rows start 16-byte aligned, so every
+// vector is naturally aligned; the last P % V columns of a row take a scalar path.
+template <typename GT, int V, int U, bool NT>
 __global__ __launch_bounds__(GRAWA_CELL) void k_local_sgd(float *__restrict__ x, int64_t ldx,
                                                           const GT *__restrict__ g, int64_t ldg,
                                                           int64_t P, float lr)
 {
     typedef typename FloatVec<V>::T XV;
     const int64_t nvec = P / V;
-    const int64_t j0 = (int64_t)blockIdx.x * (GRAWA_CELL * GRAWA_SGD_U) + threadIdx.x;
+    const int64_t j0 = (int64_t)blockIdx.x * (GRAWA_CELL * U) + threadIdx.x;
     float *xr = x + (int64_t)blockIdx.y * ldx;
     const GT *gr = g + (int64_t)blockIdx.y * ldg;
-    XV xv[GRAWA_SGD_U];
-    float gf[GRAWA_SGD_U][V];
+    XV xv[U];
+    float gf[U][V];
 #pragma unroll
-    for (int u = 0; u < GRAWA_SGD_U; ++u) {
+    for (int u = 0; u < U; ++u) {
         const int64_t j = j0 + u * GRAWA_CELL;
         if (j < nvec) {
             const XV *xp = reinterpret_cast<const XV *>(xr + j * V);
@@ -603,7 +607,7 @@ __global__ __launch_bounds__(GRAWA_CELL) void k_local_sgd(float *__restrict__ x,
     }
     __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-    for (int u = 0; u < GRAWA_SGD_U; ++u) {
+    for (int u = 0; u < U; ++u) {
         const int64_t j = j0 + u * GRAWA_CELL;
         if (j < nvec) {
             XV o = xv[u];
@@ -623,7 +627,7 @@ __global__ __launch_bounds__(GRAWA_CELL) void k_local_sgd(float *__restrict__ x,
 // grid and lane layout of k_local_sgd.  One step of SGD with Nesterov momentum and weight decay
 // (the local optimizer of Appendix B.2.2), buf = momentum buffer [K][ldb], zero before the first step:
 //     d = g + wd x ;  buf <- momentum buf + d ;  x <- x - lr (d + momentum buf).
-template <typename GT, int V, bool NT>
+template <typename GT, int V, int U, bool NT>
 __global__ __launch_bounds__(GRAWA_CELL) void k_nesterov(float *__restrict__ x, int64_t ldx,
                                                          const GT *__restrict__ g, int64_t ldg,
                                                          float *__restrict__ buf, int64_t ldb, int64_t P,
@@ -631,14 +635,14 @@ __global__ __launch_bounds__(GRAWA_CELL) void k_nesterov(float *__restrict__ x, 
 {
     typedef typename FloatVec<V>::T XV;
     const int64_t nvec = P / V;
-    const int64_t j0 = (int64_t)blockIdx.x * (GRAWA_CELL * GRAWA_SGD_U) + threadIdx.x;
+    const int64_t j0 = (int64_t)blockIdx.x * (GRAWA_CELL * U) + threadIdx.x;
     float *xr = x + (int64_t)blockIdx.y * ldx;
     float *br = buf + (int64_t)blockIdx.y * ldb;
     const GT *gr = g + (int64_t)blockIdx.y * ldg;
-    XV xv[GRAWA_SGD_U], bv[GRAWA_SGD_U];
-    float gf[GRAWA_SGD_U][V];
+    XV xv[U], bv[U];
+    float gf[U][V];
 #pragma unroll
-    for (int u = 0; u < GRAWA_SGD_U; ++u) {
+    for (int u = 0; u < U; ++u) {
         const int64_t j = j0 + u * GRAWA_CELL;
         if (j < nvec) {
             const XV *xp = reinterpret_cast<const XV *>(xr + j * V);
@@ -650,7 +654,7 @@ __global__ __launch_bounds__(GRAWA_CELL) void k_nesterov(float *__restrict__ x, 
     }
     __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-    for (int u = 0; u < GRAWA_SGD_U; ++u) {
+    for (int u = 0; u < U; ++u) {
         const int64_t j = j0 + u * GRAWA_CELL;
         if (j < nvec) {
             XV xo = xv[u], bo = bv[u];
@@ -680,6 +684,88 @@ __global__ __launch_bounds__(GRAWA_CELL) void k_nesterov(float *__restrict__ x, 
         const float b = fmaf(momentum, br[i], d);
         br[i] = b;
         xr[i] = fmaf(-lr, fmaf(momentum, b, d), xc);
+    }
+}
+
+// SGD step of one worker over one aligned block of 1024 columns, with the sums of squares of the
+// gradient (for the running norm estimate of Appendix G) taken from the values already in
+// registers: grid (ceil(P/1024), K), block 256, V * U * 256 = 1024.  The loads are issued at once;
+// only afterwards does the block look at the 1024-column tile map (tiles block_tile0[m] ..
+// block_tile0[m+1]-1 lie in aligned block m, each inside one layer) to file its sums:
+// partials[k][tile] in fp64.  Nearly every block holds one tile; a block that contains layer
+// boundaries reduces once per tile over the columns of that tile.  The last P % V columns of a row
+// are handled element by element.  fp32 gradients V = 1, U = 4; bf16 V = 4, U = 1.
+template <typename GT, int V, int U, bool NT>
+__global__ __launch_bounds__(GRAWA_CELL) void k_row_step_scored(float *__restrict__ x, int64_t ldx,
+                                                                const GT *__restrict__ g, int64_t ldg, float lr,
+                                                                int64_t P, const GrawaTile *__restrict__ tiles,
+                                                                const int32_t *__restrict__ block_tile0,
+                                                                int64_t n_tiles, double *__restrict__ partials)
+{
+    static_assert(V * U * GRAWA_CELL == 1024, "one trip covers one aligned block of the tile map");
+    typedef typename FloatVec<V>::T XV;
+    __shared__ double sm[GRAWA_BLOCK / GRAWA_WAVE];
+    const int64_t c0 = (int64_t)blockIdx.x * 1024 + (int64_t)threadIdx.x * V;
+    float *xr = x + (int64_t)blockIdx.y * ldx;
+    const GT *gr = g + (int64_t)blockIdx.y * ldg;
+    XV xv[U];
+    float gf[U][V];
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+        const int64_t c = c0 + (int64_t)u * (GRAWA_CELL * V);
+        if (c + V <= P) {
+            const XV *xp = reinterpret_cast<const XV *>(xr + c);
+            xv[u] = NT ? __builtin_nontemporal_load(xp) : *xp;
+            GradVec<GT, V, NT>::load(gr + c, gf[u]);
+        } else {
+#pragma unroll
+            for (int e = 0; e < V; ++e) gf[u][e] = 0.f;
+        }
+    }
+    const int r0 = block_tile0[blockIdx.x], r1 = block_tile0[blockIdx.x + 1];
+    __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+        const int64_t c = c0 + (int64_t)u * (GRAWA_CELL * V);
+        if (c + V <= P) {
+            XV o = xv[u];
+#pragma unroll
+            for (int e = 0; e < V; ++e) vec_set<V>(o, e, fmaf(-lr, gf[u][e], vec_get<V>(xv[u], e)));
+            XV *xp = reinterpret_cast<XV *>(xr + c);
+            if (NT) __builtin_nontemporal_store(o, xp);
+            else *xp = o;
+        } else if (V > 1 && c < P) { // the vector that holds the row's last columns
+#pragma unroll
+            for (int e = 0; e < V; ++e)
+                if (c + e < P) {
+                    gf[u][e] = Grad<GT>::one(gr + c + e);
+                    xr[c + e] = fmaf(-lr, gf[u][e], xr[c + e]);
+                }
+        }
+    }
+    double *out = partials + (int64_t)blockIdx.y * n_tiles;
+    if (r1 - r0 == 1) { // the usual case: the whole block lies in one tile
+        float acc = 0.f;
+#pragma unroll
+        for (int u = 0; u < U; ++u)
+#pragma unroll
+            for (int e = 0; e < V; ++e) acc = fmaf(gf[u][e], gf[u][e], acc);
+        const double tot = block_sum((double)acc, sm);
+        if (threadIdx.x == 0) out[r0] = tot;
+    } else {
+        for (int r = r0; r < r1; ++r) {
+            const int64_t lo = tiles[r].start, hi = lo + tiles[r].len;
+            float acc = 0.f;
+#pragma unroll
+            for (int u = 0; u < U; ++u)
+#pragma unroll
+                for (int e = 0; e < V; ++e) {
+                    const int64_t c = c0 + (int64_t)u * (GRAWA_CELL * V) + e;
+                    acc = (c >= lo && c < hi) ? fmaf(gf[u][e], gf[u][e], acc) : acc;
+                }
+            const double tot = block_sum((double)acc, sm);
+            if (threadIdx.x == 0) out[r] = tot;
+        }
     }
 }
 
@@ -926,38 +1012,67 @@ hipError_t grawa_launch_center_pull(const grawa_plan *p, float *x, int64_t ldx, 
 hipError_t grawa_launch_local_sgd(float *x, int64_t ldx, const void *g, int64_t ldg, grawa_dtype_t dt,
                                   int K, int64_t P, float lr, hipStream_t s)
 {
-    const int64_t per_block = GRAWA_CELL * GRAWA_SGD_U * (dt == GRAWA_BF16 ? 4 : 1);
+    const int64_t per_block = dt == GRAWA_BF16 ? GRAWA_CELL * GRAWA_SGD_U_BF16 * GRAWA_SGD_V_BF16
+                                               : GRAWA_CELL * GRAWA_SGD_U_F32 * GRAWA_SGD_V_F32;
     int64_t gx = (P + per_block - 1) / per_block;
     if (gx < 1) gx = 1;
     const dim3 grid((unsigned)gx, (unsigned)K), block(GRAWA_CELL);
     const bool nt = (int64_t)K * P * 4 > GRAWA_STREAMING_MIN_BYTES && rows_line_aligned(x, ldx, 4) &&
                     rows_line_aligned(g, ldg, dt == GRAWA_BF16 ? 2 : 4);
+#define GRAWA_SGD_GO(GT, V, U, NT) k_local_sgd<GT, V, U, NT><<<grid, block, 0, s>>>(x, ldx, (const GT *)g, ldg, P, lr)
     if (dt == GRAWA_BF16) {
-        if (nt) k_local_sgd<uint16_t, 4, true><<<grid, block, 0, s>>>(x, ldx, (const uint16_t *)g, ldg, P, lr);
-        else k_local_sgd<uint16_t, 4, false><<<grid, block, 0, s>>>(x, ldx, (const uint16_t *)g, ldg, P, lr);
+        if (nt) GRAWA_SGD_GO(uint16_t, GRAWA_SGD_V_BF16, GRAWA_SGD_U_BF16, true);
+        else GRAWA_SGD_GO(uint16_t, GRAWA_SGD_V_BF16, GRAWA_SGD_U_BF16, false);
     } else {
-        if (nt) k_local_sgd<float, 1, true><<<grid, block, 0, s>>>(x, ldx, (const float *)g, ldg, P, lr);
-        else k_local_sgd<float, 1, false><<<grid, block, 0, s>>>(x, ldx, (const float *)g, ldg, P, lr);
+        if (nt) GRAWA_SGD_GO(float, GRAWA_SGD_V_F32, GRAWA_SGD_U_F32, true);
+        else GRAWA_SGD_GO(float, GRAWA_SGD_V_F32, GRAWA_SGD_U_F32, false);
     }
+#undef GRAWA_SGD_GO
     return hipGetLastError();
 }
 
 hipError_t grawa_launch_nesterov(float *x, int64_t ldx, const void *g, int64_t ldg, grawa_dtype_t dt, float *buf,
                                  int64_t ldb, int K, int64_t P, float lr, float momentum, float wd, hipStream_t s)
 {
-    const int64_t per_block = GRAWA_CELL * GRAWA_SGD_U * (dt == GRAWA_BF16 ? 4 : 1);
+    const int64_t per_block = dt == GRAWA_BF16 ? GRAWA_CELL * GRAWA_SGD_U_BF16 * GRAWA_SGD_V_BF16
+                                               : GRAWA_CELL * GRAWA_SGD_U_F32 * GRAWA_SGD_V_F32;
     int64_t gx = (P + per_block - 1) / per_block;
     if (gx < 1) gx = 1;
     const dim3 grid((unsigned)gx, (unsigned)K), block(GRAWA_CELL);
     const bool nt = (int64_t)K * P * 4 > GRAWA_STREAMING_MIN_BYTES && rows_line_aligned(x, ldx, 4) &&
                     rows_line_aligned(buf, ldb, 4) && rows_line_aligned(g, ldg, dt == GRAWA_BF16 ? 2 : 4);
+#define GRAWA_NAG_GO(GT, V, U, NT) \
+    k_nesterov<GT, V, U, NT><<<grid, block, 0, s>>>(x, ldx, (const GT *)g, ldg, buf, ldb, P, lr, momentum, wd)
     if (dt == GRAWA_BF16) {
-        if (nt) k_nesterov<uint16_t, 4, true><<<grid, block, 0, s>>>(x, ldx, (const uint16_t *)g, ldg, buf, ldb, P, lr, momentum, wd);
-        else k_nesterov<uint16_t, 4, false><<<grid, block, 0, s>>>(x, ldx, (const uint16_t *)g, ldg, buf, ldb, P, lr, momentum, wd);
+        if (nt) GRAWA_NAG_GO(uint16_t, GRAWA_SGD_V_BF16, GRAWA_SGD_U_BF16, true);
+        else GRAWA_NAG_GO(uint16_t, GRAWA_SGD_V_BF16, GRAWA_SGD_U_BF16, false);
     } else {
-        if (nt) k_nesterov<float, 1, true><<<grid, block, 0, s>>>(x, ldx, (const float *)g, ldg, buf, ldb, P, lr, momentum, wd);
-        else k_nesterov<float, 1, false><<<grid, block, 0, s>>>(x, ldx, (const float *)g, ldg, buf, ldb, P, lr, momentum, wd);
+        if (nt) GRAWA_NAG_GO(float, GRAWA_SGD_V_F32, GRAWA_SGD_U_F32, true);
+        else GRAWA_NAG_GO(float, GRAWA_SGD_V_F32, GRAWA_SGD_U_F32, false);
     }
+#undef GRAWA_NAG_GO
+    return hipGetLastError();
+}
+
+// Per-row scored step; tiles / block_tile0: the plan's 1024-column tile map and its index by aligned block.
+hipError_t grawa_launch_row_step_scored(float *x, int64_t ldx, const void *g, int64_t ldg, grawa_dtype_t dt,
+                                        float lr, const GrawaTile *tiles, const int32_t *block_tile0,
+                                        int64_t n_tiles, int K, int64_t P, double *partials, hipStream_t s)
+{
+    const dim3 grid((unsigned)((P + 1023) / 1024), (unsigned)K), block(GRAWA_CELL);
+    const bool nt = (int64_t)K * P * 4 > GRAWA_STREAMING_MIN_BYTES && rows_line_aligned(x, ldx, 4) &&
+                    rows_line_aligned(g, ldg, dt == GRAWA_BF16 ? 2 : 4);
+#define GRAWA_RSS_GO(GT, V, U, NT)                                                                             \
+    k_row_step_scored<GT, V, U, NT><<<grid, block, 0, s>>>(x, ldx, (const GT *)g, ldg, lr, P, tiles, block_tile0, \
+                                                           n_tiles, partials)
+    if (dt == GRAWA_BF16) {
+        if (nt) GRAWA_RSS_GO(uint16_t, 4, 1, true);
+        else GRAWA_RSS_GO(uint16_t, 4, 1, false);
+    } else {
+        if (nt) GRAWA_RSS_GO(float, 1, 4, true);
+        else GRAWA_RSS_GO(float, 1, 4, false);
+    }
+#undef GRAWA_RSS_GO
     return hipGetLastError();
 }
 

@@ -66,6 +66,7 @@ def lib():
         "grawa_lsgd_update": (it, [vp, vp, i64, vp, fl, vp, vp, vp]),
         "grawa_plan_profile": (it, [vp, it]),
         "grawa_plan_profile_read": (it, [vp, C.POINTER(it), C.POINTER(dbl), C.POINTER(dbl)]),
+        "grawa_plan_profile_read_call": (it, [vp, it, C.POINTER(dbl), C.POINTER(dbl), C.POINTER(dbl)]),
         "grawa_stream_copy": (it, [vp, vp, i64, vp]),
     }
     for name, (res, args) in sig.items():
@@ -244,6 +245,12 @@ class Plan:
         n, a, b = C.c_int(), C.c_double(), C.c_double()
         _check(lib().grawa_plan_profile_read(self._h, C.byref(n), C.byref(a), C.byref(b)), "grawa_plan_profile_read")
         return {"calls": n.value, "norm_ms": a.value, "pull_ms": b.value}
+
+    def profile_read_call(self, i):
+        a, b, c = C.c_double(), C.c_double(), C.c_double()
+        _check(lib().grawa_plan_profile_read_call(self._h, int(i), C.byref(a), C.byref(b), C.byref(c)),
+               "grawa_plan_profile_read_call")
+        return {"norm_ms": a.value, "pull_ms": b.value, "span_ms": c.value}
 
 
 def local_sgd(x, g, lr, P=None, stream=None):

@@ -73,7 +73,8 @@ def test_local_sgd_prox_limits():
 @pytest.mark.parametrize("policy", ["lgrawa", "mgrawa"])
 @pytest.mark.parametrize("K,dtype,steps,prox", [(4, "f32", 1, False), (4, "f32", 3, True), (8, "bf16", 4, True),
                                                (16, "f32", 2, False), (32, "f32", 2, True), (5, "bf16", 5, False),
-                                               (40, "f32", 2, True)])
+                                               (40, "f32", 2, True), (70, "f32", 2, False), (3, "bf16", 2, False),
+                                               (33, "bf16", 1, False)])
 def test_local_round(policy, K, dtype, steps, prox):
     sizes = RAGGED if K <= 16 else RAGGED[:8]
     w, x, g0 = W.make_small(400 + K, K, sizes, grad_dtype=dtype, ld_pad=0, device=DEV)
