@@ -91,6 +91,29 @@ def time_config(torch, grawa, W, idx, variant, steps, warmup):
             call_update(plan, w, x, g, variant)
         torch.cuda.synchronize()
         t1 = time.perf_counter()
+        # the same update recorded once into a HIP graph and replayed `steps` times (what a launch-bound
+        # caller would do; reported beside the eager figure, never instead of it)
+        graph_ms = None
+        try:
+            side = torch.cuda.Stream()
+            side.wait_stream(torch.cuda.current_stream())
+            with torch.cuda.stream(side):
+                call_update(plan, w, x, g, variant)
+            torch.cuda.current_stream().wait_stream(side)
+            torch.cuda.synchronize()
+            graph = torch.cuda.CUDAGraph()
+            with torch.cuda.graph(graph):
+                call_update(plan, w, x, g, variant)
+            graph.replay()
+            torch.cuda.synchronize()
+            g0 = time.perf_counter()
+            for _ in range(steps):
+                graph.replay()
+            torch.cuda.synchronize()
+            graph_ms = (time.perf_counter() - g0) * 1e3 / steps
+            del graph
+        except RuntimeError as e:                            # reported, not fatal: the eager figure stands
+            print("bench.py: graph replay skipped: %s" % e, file=sys.stderr)
         # the same steps again with start/stop events attached to the two big kernels
         plan.profile(True)
         for _ in range(steps):
@@ -115,6 +138,7 @@ def time_config(torch, grawa, W, idx, variant, steps, warmup):
         "pull_kernel_ms": pull_ms, "pull_kernel_GBps": pull_bytes / (pull_ms * 1e-3) / 1e9 if pull_ms > 0 else None,
         "pull_kernel_bytes": pull_bytes, "tile_elems": info["tile_elems"], "n_tiles": info["n_tiles"],
         # per update, first kernel start to last kernel end on the device (the event pass)
+        "graph_replay_ms_per_step": graph_ms,
         "device_ms": spread([c["span_ms"] for c in per_call]),
         "pull_kernel_ms_spread": spread([c["pull_ms"] for c in per_call]),
     }
@@ -296,7 +320,8 @@ def main():
                    "grad_dtype": w.grad_dtype, "lambda": w.lam, "bytes_per_update": stats["model_bytes"],
                    "tile_elems": stats["tile_elems"]},
         "frac_of_hbm_peak": stats["frac_of_peak"], "updates_per_s": stats["updates_per_s"],
-        "device_ms_per_update": stats["device_ms"], "roofline": roofline,
+        "device_ms_per_update": stats["device_ms"], "graph_replay_ms_per_step": stats["graph_replay_ms_per_step"],
+        "roofline": roofline,
     }
     out["copy_kernel"] = copy_ceiling(torch, grawa)
     torch.cuda.empty_cache()
@@ -305,14 +330,16 @@ def main():
         for i in range(W.N_CONFIGS):
             if i == a.config:
                 sweep.append({k: stats[k] for k in ("workload", "variant", "ms_per_step", "updates_per_s", "GBps",
-                                                     "frac_of_peak", "pull_kernel_GBps", "norm_kernel_GBps")})
+                                                     "frac_of_peak", "pull_kernel_GBps", "norm_kernel_GBps",
+                                                     "graph_replay_ms_per_step")})
                 continue
             for var in W.config(i).variants:
                 s, x, g, _ = time_config(torch, grawa, W, i, var, a.steps, a.warmup)
                 del x, g
                 torch.cuda.empty_cache()
                 sweep.append({k: s[k] for k in ("workload", "variant", "ms_per_step", "updates_per_s", "GBps",
-                                                 "frac_of_peak", "pull_kernel_GBps", "norm_kernel_GBps")})
+                                                 "frac_of_peak", "pull_kernel_GBps", "norm_kernel_GBps",
+                                                 "graph_replay_ms_per_step")})
         out["all_configs"] = sweep
     if not a.no_phases and not a.no_sweep:
         out["phases"] = time_phases(torch, grawa, W, a.config, a.steps, a.warmup)

@@ -253,3 +253,35 @@ def test_side_stream():
         s.synchronize()
     ref = orc.lgrawa_update(xh, gh, w.offsets, 0.2)
     assert_params_close(x.cpu().numpy()[:, :w.P], ref["x"], w.offsets, TIGHT, "side stream", operand_scale(xh[:, :w.P]))
+
+
+def test_update_replayed_from_a_captured_graph():
+    # The calls launch kernels only (no allocation, no host synchronisation, no memset node), so a
+    # caller may record them into a HIP graph.  Replays, with eager work in between, must give
+    # bit for bit what the eager call gives.
+    w, x, g = W.make_small(72, 8, RAGGED, device=DEV)
+    P = w.P
+    say("graph capture")
+    cen_e, cen_g = torch.empty(W.round_up(P, 4), device=DEV), torch.empty(W.round_up(P, 4), device=DEV)
+    wts_e, wts_g = torch.empty((8, w.L), device=DEV), torch.empty((8, w.L), device=DEV)
+    xs = x.clone()
+    with grawa.Plan(8, P, w.offsets) as plan:
+        side = torch.cuda.Stream()
+        side.wait_stream(torch.cuda.current_stream())
+        with torch.cuda.stream(side):                      # warm-up outside the capture
+            plan.lgrawa_update_sgd(xs[:, :P], g[:, :P], 0.3, g[:, :P], 0.05)
+        torch.cuda.current_stream().wait_stream(side)
+        torch.cuda.synchronize()
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph):
+            plan.lgrawa_update_sgd(xs[:, :P], g[:, :P], 0.3, g[:, :P], 0.05, center_out=cen_g, weights_out=wts_g)
+            plan.mgrawa_update(xs[:, :P], g[:, :P], 0.1)
+        for rep in range(3):
+            xe = x.clone() + rep                            # eager work between the replays
+            xs.copy_(xe)
+            plan.lgrawa_update_sgd(xe[:, :P], g[:, :P], 0.3, g[:, :P], 0.05, center_out=cen_e, weights_out=wts_e)
+            plan.mgrawa_update(xe[:, :P], g[:, :P], 0.1)
+            graph.replay()
+            torch.cuda.synchronize()
+            assert torch.equal(xs, xe), "replay %d differs from the eager call" % rep
+            assert torch.equal(cen_g[:P], cen_e[:P]) and torch.equal(wts_g, wts_e)
