@@ -142,8 +142,22 @@ const char *grawa_status_string(grawa_status_t s)
     return "unknown status";
 }
 
+static grawa_status_t plan_create_impl(grawa_plan_t **out, int K, int64_t P, int L,
+                                       const int64_t *layer_offsets_host);
+
 grawa_status_t grawa_plan_create(grawa_plan_t **out, int K, int64_t P, int L,
                                  const int64_t *layer_offsets_host)
+{
+    try { // the host-side maps live in std::vector; no exception may cross the C boundary
+        return plan_create_impl(out, K, P, L, layer_offsets_host);
+    } catch (...) {
+        if (out) *out = nullptr;
+        return GRAWA_ERR_WORKSPACE;
+    }
+}
+
+static grawa_status_t plan_create_impl(grawa_plan_t **out, int K, int64_t P, int L,
+                                       const int64_t *layer_offsets_host)
 {
     if (!out) return GRAWA_ERR_INVALID_ARG;
     *out = nullptr;

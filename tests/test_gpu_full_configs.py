@@ -15,7 +15,7 @@ import torch
 
 from oracle import grawa_oracle as orc
 from paper_2403_04206_amd import grawa, workloads as W
-from parity_util import TIGHT, assert_params_close, assert_table_close, operand_scale
+from parity_util import TIGHT, assert_params_close, assert_table_close, grads_to_f64, operand_scale
 
 pytestmark = pytest.mark.gpu
 DEV = "cuda:0"
@@ -220,3 +220,61 @@ def test_config2_local_round_full_size():
         assert_params_close(x[:, i0:i1].cpu().numpy(), want, off, TIGHT, "x window %d" % i0, scale, col0=i0)
         assert_params_close(cen[i0:i1].cpu().numpy(), c, off, TIGHT, "center window %d" % i0, scale, col0=i0)
     assert torch.equal(x[:, P:], x0[:, P:])
+
+
+@pytest.mark.parametrize("cfg_index", [2, 3])
+def test_full_size_nesterov_easgd_lsgd(cfg_index):
+    # The local optimizer of the experiments (two steps, so the momentum buffer is used) and the two
+    # Appendix F phases at the benchmark's sizes, on sampled windows (every step is column-local once
+    # the leader / the weights are known).
+    w = W.config(cfg_index)
+    P, K = w.P, w.K
+    say("config %d nesterov/easgd/lsgd K=%d P=%d grads=%s" % (cfg_index, K, P, w.grad_dtype))
+    x, g = W.make_inputs(w, device=DEV)
+    x0 = x.clone()
+    rng = np.random.default_rng(300 + cfg_index)
+    wins = sample_windows(w, rng, n_random=10)
+    lr, mom, wd, lam, rho = 0.05, 0.9, 5e-4, 0.3, 0.25
+
+    buf = torch.zeros_like(x)
+    grawa.local_nesterov(x[:, :P], g[:, :P], buf[:, :P], lr, mom, wd)
+    grawa.local_nesterov(x[:, :P], g[:, :P], buf[:, :P], lr, mom, wd)
+    torch.cuda.synchronize()
+    for i0 in wins:
+        i1 = min(P, i0 + WINDOW)
+        xs = np.ascontiguousarray(x0[:, i0:i1].cpu().numpy())
+        gs = W.to_numpy_grads(g[:, i0:i1].contiguous())
+        rx, rb = orc.nesterov_sgd(xs, np.zeros((K, i1 - i0)), gs, lr, mom, wd)
+        rx, rb = orc.nesterov_sgd(rx, rb, gs, lr, mom, wd)
+        sc = operand_scale(xs, gs, lr * (2 + 3 * mom))
+        off = np.array([0, i1 - i0])
+        assert_params_close(x[:, i0:i1].cpu().numpy(), rx, off, 2 * TIGHT, "nesterov x [%d,%d)" % (i0, i1), sc)
+        sb = (1 + mom) * (np.abs(grads_to_f64(gs)).max(axis=0) + wd * sc)
+        assert_params_close(buf[:, i0:i1].cpu().numpy(), rb, off, 2 * TIGHT, "nesterov buf [%d,%d)" % (i0, i1), sb)
+    assert torch.equal(x[:, P:], x0[:, P:]) and not buf[:, P:].any()
+    del buf
+
+    x.copy_(x0)
+    cen = 0.05 * torch.randn(W.round_up(P, 256), device=DEV, generator=torch.Generator(device=DEV).manual_seed(5))
+    cen0 = cen.clone()
+    losses = torch.rand(K, device=DEV, generator=torch.Generator(device=DEV).manual_seed(6))
+    lead = torch.zeros(1, dtype=torch.int32, device=DEV)
+    x2 = x0.clone()
+    with grawa.Plan(K, P, w.offsets) as plan:
+        plan.easgd_update(x[:, :P], lam, rho, cen)
+        plan.lsgd_update(x2[:, :P], losses, lam, leader_out=lead)
+        torch.cuda.synchronize()
+    want_lead = int(np.argmin(losses.cpu().numpy()))
+    assert int(lead.item()) == want_lead
+    for i0 in wins:
+        i1 = min(P, i0 + WINDOW)
+        xs = np.ascontiguousarray(x0[:, i0:i1].cpu().numpy())
+        off = np.array([0, i1 - i0])
+        rx, rc = orc.easgd_update(xs, cen0[i0:i1].cpu().numpy().astype(np.float64), lam, rho)
+        sc = np.maximum(operand_scale(xs), np.abs(cen0[i0:i1].cpu().numpy().astype(np.float64)))
+        assert_params_close(x[:, i0:i1].cpu().numpy(), rx, off, TIGHT, "easgd x [%d,%d)" % (i0, i1), sc)
+        assert_params_close(cen[i0:i1].cpu().numpy(), rc, off, TIGHT, "easgd center [%d,%d)" % (i0, i1), sc)
+        rx, _ = orc.lsgd_update(xs, losses.cpu().numpy().astype(np.float64), lam)
+        assert_params_close(x2[:, i0:i1].cpu().numpy(), rx, off, TIGHT, "lsgd x [%d,%d)" % (i0, i1), operand_scale(xs))
+    assert torch.equal(x2[want_lead], x0[want_lead])          # the leader does not move
+    assert torch.equal(x[:, P:], x0[:, P:]) and torch.equal(cen[P:], cen0[P:])
