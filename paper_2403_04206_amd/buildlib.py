@@ -4,18 +4,21 @@ from __future__ import annotations
 import os
 import shutil
 import subprocess
+from concurrent.futures import ThreadPoolExecutor
 
 PKG = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(PKG)
 CSRC = os.path.join(PKG, "csrc")
 LIB = os.path.join(PKG, "libgrawa.so")
-SOURCES = [os.path.join(CSRC, "grawa_api.cpp"), os.path.join(CSRC, "grawa_kernels.hip")]
-HEADERS = [os.path.join(CSRC, "grawa_internal.h"), os.path.join(ROOT, "include", "grawa.h")]
+BUILD = os.path.join(PKG, "_build")
+SOURCES = [os.path.join(CSRC, n) for n in ("grawa_api.cpp", "grawa_norms.hip", "grawa_pull.hip", "grawa_local.hip")]
+HEADERS = [os.path.join(CSRC, "grawa_internal.h"), os.path.join(CSRC, "grawa_device.h"),
+           os.path.join(ROOT, "include", "grawa.h")]
 
 # Packed fp32 instructions are switched off for all device code (a hipcc flag, not a host one;
 # the host pass warns that it does not know the feature, which is harmless).
 HIPCC_FLAGS = [
-    "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared", "-x", "hip",
+    "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-x", "hip",
     "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
     "-Wall", "-Wno-unused-command-line-argument",
 ]
@@ -36,21 +39,43 @@ def needs_build() -> bool:
 
 
 def build(force: bool = True, verbose: bool = False) -> str:
-    """Compile the library; returns its path.  force=False skips an up-to-date build."""
+    """Compile the library (one object per source, in parallel, then one link); returns its path.
+    force=False skips an up-to-date build."""
     if not force and not needs_build():
         return LIB
-    tmp = LIB + ".tmp.%d" % os.getpid()
-    cmd = [hipcc()] + HIPCC_FLAGS + ["-I", os.path.join(ROOT, "include"), "-I", CSRC, "-o", tmp] + SOURCES
-    if verbose:
-        print(" ".join(cmd), flush=True)
-    res = subprocess.run(cmd, stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True)
-    if res.returncode != 0:
-        if os.path.exists(tmp):
-            os.remove(tmp)
-        raise RuntimeError("hipcc failed:\n" + res.stdout)
-    if verbose and res.stdout.strip():
-        print(res.stdout)
-    os.replace(tmp, LIB)
+    os.makedirs(BUILD, exist_ok=True)
+    tag = ".tmp.%d" % os.getpid()
+    inc = ["-I", os.path.join(ROOT, "include"), "-I", CSRC]
+
+    def compile_one(src):
+        obj = os.path.join(BUILD, os.path.basename(src) + tag + ".o")
+        cmd = [hipcc()] + HIPCC_FLAGS + inc + ["-c", src, "-o", obj]
+        if verbose:
+            print(" ".join(cmd), flush=True)
+        res = subprocess.run(cmd, stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True)
+        return obj, res
+
+    with ThreadPoolExecutor(max_workers=min(4, len(SOURCES))) as pool:
+        results = list(pool.map(compile_one, SOURCES))
+    objs = [o for o, _ in results]
+    tmp = LIB + tag
+    try:
+        for _, res in results:
+            if res.returncode != 0:
+                raise RuntimeError("hipcc failed:\n" + res.stdout)
+            if verbose and res.stdout.strip():
+                print(res.stdout)
+        link = [hipcc(), "--offload-arch=gfx950", "-shared", "-fPIC", "-o", tmp] + objs
+        if verbose:
+            print(" ".join(link), flush=True)
+        res = subprocess.run(link, stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True)
+        if res.returncode != 0:
+            raise RuntimeError("link failed:\n" + res.stdout)
+        os.replace(tmp, LIB)
+    finally:
+        for f in objs + [tmp]:
+            if os.path.exists(f):
+                os.remove(f)
     return LIB
 
 

@@ -1,6 +1,6 @@
 // Host side of the C ABI declared in include/grawa.h: argument checks, the plan (tile map
 // and workspace) and the launch sequence of each entry point.  Nothing here computes any
-// part of the update; every step runs in the kernels of grawa_kernels.hip.
+// part of the update; every step runs in the kernels of grawa_norms.hip, grawa_pull.hip and grawa_local.hip.
 #include <cmath>
 #include <cstdlib>
 #include <cstring>

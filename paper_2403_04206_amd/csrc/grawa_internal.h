@@ -1,5 +1,5 @@
-// Internal declarations shared by the host API (grawa_api.cpp) and the kernel
-// translation unit (grawa_kernels.hip).  Not installed; the public ABI is include/grawa.h.
+// Internal declarations shared by the host API (grawa_api.cpp) and the kernel files
+// (grawa_norms.hip, grawa_pull.hip, grawa_local.hip).  Not installed; the public ABI is include/grawa.h.
 #ifndef GRAWA_INTERNAL_H
 #define GRAWA_INTERNAL_H
 
@@ -52,7 +52,7 @@ struct grawa_plan {
     hipEvent_t *ev; // 4 per slot: norm begin/end, pull begin/end
 };
 
-// Launchers (defined in grawa_kernels.hip).  All return the hipError_t of the launch.
+// Launchers (defined next to their kernels).  All return the hipError_t of the launch.
 // e0/e1: optional start/stop events of the launch itself (null when not profiling).
 hipError_t grawa_launch_sumsq(const grawa_plan *p, const void *g, int64_t ldg, grawa_dtype_t dt,
                               hipStream_t s, hipEvent_t e0, hipEvent_t e1);

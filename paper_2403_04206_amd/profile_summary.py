@@ -33,7 +33,7 @@ COPY_BYTES = 1 << 31
 
 def kernel_source_hash() -> str:
     h = hashlib.sha256()
-    for name in ("grawa_kernels.hip", "grawa_api.cpp", "grawa_internal.h"):
+    for name in sorted(os.listdir(os.path.join(PKG, "csrc"))):
         with open(os.path.join(PKG, "csrc", name), "rb") as f:
             h.update(f.read())
     return h.hexdigest()[:16]

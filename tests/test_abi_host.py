@@ -132,3 +132,14 @@ def test_product_package_never_imports_the_oracle():
             if fn.endswith((".py", ".cpp", ".hip", ".h")):
                 text = open(os.path.join(dirpath, fn)).read()
                 assert "oracle" not in text.lower(), "%s mentions the oracle" % fn
+
+
+def test_bench_refuses_more_than_one_gpu():
+    # The benchmark measures one GPU's throughput; asking for more must end with a message, not a run.
+    import subprocess
+    import sys
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    res = subprocess.run([sys.executable, os.path.join(root, "bench.py"), "--gpus", "2"], capture_output=True, text=True,
+                         timeout=120)
+    assert res.returncode != 0
+    assert "ONE GPU" in res.stderr and res.stdout.strip() == ""
