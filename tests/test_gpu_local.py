@@ -77,10 +77,12 @@ def test_local_sgd_prox_limits():
                                                (33, "bf16", 1, False)])
 def test_local_round(policy, K, dtype, steps, prox):
     sizes = RAGGED if K <= 16 else RAGGED[:8]
-    w, x, g0 = W.make_small(400 + K, K, sizes, grad_dtype=dtype, ld_pad=0, device=DEV)
+    ld_pad = 8 if K in (3, 5, 70) else 0                 # rows that are 16-byte but not line aligned
+    w, x, g0 = W.make_small(400 + K, K, sizes, grad_dtype=dtype, ld_pad=ld_pad, device=DEV)
     P, L = w.P, w.L
     say("local round policy=%s K=%d dtype=%s steps=%d prox=%s P=%d" % (policy, K, dtype, steps, prox, P))
-    grads = [g0] + [W.make_small(500 + 10 * K + t, K, sizes, grad_dtype=dtype, device=DEV)[2] for t in range(1, steps)]
+    grads = [g0] + [W.make_small(500 + 10 * K + t, K, sizes, grad_dtype=dtype, ld_pad=ld_pad, device=DEV)[2]
+                    for t in range(1, steps)]
     xh = W.to_numpy_params(x)
     ghs = [W.to_numpy_grads(g) for g in grads]
     lr, lam, gamma, mu, tau = 0.05, 0.3, 0.9, 0.05, 16.0
