@@ -163,7 +163,7 @@ grawa_status_t grawa_lgrawa_update_sgd(grawa_plan_t *plan, float *x, int64_t ldx
  * center: device float [P], the center stored by the last distributed phase
  * (the center_out of an update call); it is read once per column for all K
  * workers.  mu is the proximity strength, tau the communication period;
- * 0 <= mu <= tau, tau > 0.  Needs no plan.  K <= 64 (UNSUPPORTED beyond).
+ * 0 <= mu <= tau, tau > 0.  Needs no plan.
  */
 grawa_status_t grawa_local_sgd_prox(float *x, int64_t ldx, const void *g, int64_t ldg,
                                     grawa_dtype_t g_dtype, int K, int64_t P, float lr,
@@ -179,7 +179,7 @@ grawa_status_t grawa_local_sgd_prox(float *x, int64_t ldx, const void *g, int64_
  *   t <- t + 1 ;  g_mvg <- gamma g_mvg + (1 - gamma) g_cur          (kept in the plan, fp64)
  *   x_k <- x_k - lr g_k ;  if center != NULL: x_k <- (1 - mu/tau) x_k + (mu/tau) center
  * 0 < gamma < 1, and gamma must not change between two communications
- * (INVALID_ARG).  With a center K <= 64 (UNSUPPORTED beyond); without, any K of the plan.
+ * (INVALID_ARG).
  *
  * grawa_local_lgrawa_update / grawa_local_mgrawa_update: the communication step:
  *   g_est = gamma g_mvg / (1 - gamma^t)            (as printed, leading gamma included)

@@ -391,12 +391,13 @@ grawa_status_t grawa_local_sgd(float *x, int64_t ldx, const void *g, int64_t ldg
                                int64_t P, float lr, void *stream)
 {
     if (!x || K < 1 || P < 1 || ldx < P) return GRAWA_ERR_INVALID_ARG;
-    if (K > 65535 || P >= ((int64_t)1 << 32)) return GRAWA_ERR_UNSUPPORTED;
+    if (K > 65535 || P >= ((int64_t)1 << 32)) return GRAWA_ERR_UNSUPPORTED; /* grid.y; 2^22 column blocks */
     if (!aligned16(x) || (ldx % 4) != 0) return GRAWA_ERR_ALIGNMENT;
     grawa_status_t st = check_grads(P, g, ldg, dt);
     if (st != GRAWA_OK) return st;
     if (!std::isfinite(lr)) return GRAWA_ERR_INVALID_ARG;
-    GRAWA_TRY_HIP(grawa_launch_local_sgd(x, ldx, g, ldg, dt, K, P, lr, static_cast<hipStream_t>(stream)));
+    GRAWA_TRY_HIP(grawa_launch_row_step(x, ldx, g, ldg, dt, lr, nullptr, 0.f, K, P, nullptr, nullptr, 0, nullptr,
+                                        static_cast<hipStream_t>(stream)));
     return GRAWA_OK;
 }
 
@@ -453,16 +454,14 @@ grawa_status_t grawa_local_sgd_prox(float *x, int64_t ldx, const void *g, int64_
                                     int64_t P, float lr, const float *center, float mu, float tau, void *stream)
 {
     if (!x || !center || K < 1 || P < 1 || ldx < P) return GRAWA_ERR_INVALID_ARG;
-    if (K > 64 || P >= ((int64_t)1 << 32)) return GRAWA_ERR_UNSUPPORTED;
+    if (K > 65535 || P >= ((int64_t)1 << 32)) return GRAWA_ERR_UNSUPPORTED; /* grid.y; 2^22 column blocks */
     if (!aligned16(x) || (ldx % 4) != 0 || !aligned16(center)) return GRAWA_ERR_ALIGNMENT;
     grawa_status_t st = check_grads(P, g, ldg, dt);
     if (st != GRAWA_OK) return st;
     if (!std::isfinite(lr) || !std::isfinite(mu) || !std::isfinite(tau) || !(tau > 0.f) || mu < 0.f || mu > tau)
         return GRAWA_ERR_INVALID_ARG;
-    const int T = 256; /* short tiles: see k_rows_step */
-    const int64_t nt = (P + T - 1) / T;
-    GRAWA_TRY_HIP(grawa_launch_rows_step(x, ldx, g, ldg, dt, lr, center, mu / tau, nullptr, T, nt, K, P, nullptr,
-                                         static_cast<hipStream_t>(stream)));
+    GRAWA_TRY_HIP(grawa_launch_row_step(x, ldx, g, ldg, dt, lr, center, mu / tau, K, P, nullptr, nullptr, 0, nullptr,
+                                        static_cast<hipStream_t>(stream)));
     return GRAWA_OK;
 }
 
@@ -473,7 +472,6 @@ grawa_status_t grawa_local_step_scored(grawa_plan_t *p, float *x, int64_t ldx, c
     grawa_status_t st;
     if ((st = check_params(p, x, ldx)) != GRAWA_OK) return st;
     if ((st = check_grads(p->P, g, ldg, dt)) != GRAWA_OK) return st;
-    if (center ? p->K > 64 : p->K > 65535) return GRAWA_ERR_UNSUPPORTED;
     if (!std::isfinite(lr) || !(gamma > 0.f) || !(gamma < 1.f)) return GRAWA_ERR_INVALID_ARG;
     if (p->local_t > 0 && (double)gamma != p->local_gamma) return GRAWA_ERR_INVALID_ARG; /* one gamma per round */
     float w = 0.f;
@@ -486,12 +484,8 @@ grawa_status_t grawa_local_step_scored(grawa_plan_t *p, float *x, int64_t ldx, c
     DeviceGuard guard(p->device);
     if (!guard.ok) return GRAWA_ERR_HIP;
     hipStream_t s = static_cast<hipStream_t>(stream);
-    if (center) /* all K rows of a tile in one block: the stored center is read once */
-        GRAWA_TRY_HIP(grawa_launch_rows_step(x, ldx, g, ldg, dt, lr, center, w, p->d_rtiles, 1024, p->n_rtiles,
-                                             p->K, p->P, p->d_partials, s));
-    else /* row by row: the faster shape when nothing is shared between the rows */
-        GRAWA_TRY_HIP(grawa_launch_row_step_scored(x, ldx, g, ldg, dt, lr, p->d_rtiles, p->d_block_rtile0,
-                                                   p->n_rtiles, p->K, p->P, p->d_partials, s));
+    GRAWA_TRY_HIP(grawa_launch_row_step(x, ldx, g, ldg, dt, lr, center, w, p->K, p->P, p->d_rtiles,
+                                        p->d_block_rtile0, p->n_rtiles, p->d_partials, s));
     GRAWA_TRY_HIP(grawa_launch_finalize_layers(p, nullptr, nullptr, s, 1, (double)gamma));
     p->local_t += 1;
     p->local_gamma = (double)gamma;

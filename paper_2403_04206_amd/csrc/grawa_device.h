@@ -148,6 +148,18 @@ template <typename GT, int V, bool NT> struct GradVec;
 template <bool NT> struct GradVec<float, 1, NT> {
     static __device__ __forceinline__ void load(const float *p, float (&f)[1]) { f[0] = NT ? __builtin_nontemporal_load(p) : *p; }
 };
+template <bool NT> struct GradVec<float, 4, NT> {
+    static __device__ __forceinline__ void load(const float *p, float (&f)[4])
+    {
+        typedef float v4f __attribute__((ext_vector_type(4)));
+        const v4f *q = reinterpret_cast<const v4f *>(p);
+        const v4f w = NT ? __builtin_nontemporal_load(q) : *q;
+        f[0] = w.x;
+        f[1] = w.y;
+        f[2] = w.z;
+        f[3] = w.w;
+    }
+};
 template <bool NT> struct GradVec<uint16_t, 2, NT> {
     static __device__ __forceinline__ void load(const uint16_t *p, float (&f)[2])
     {

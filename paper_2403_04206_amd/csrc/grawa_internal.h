@@ -61,9 +61,9 @@ hipError_t grawa_launch_finalize_layers(const grawa_plan *p, float *norms_user, 
 hipError_t grawa_launch_local_weights(const grawa_plan *p, double scale, int per_layer, float *beta_user,
                                       float *est_user, hipStream_t s);
 hipError_t grawa_launch_zero_estimate(const grawa_plan *p, hipStream_t s);
-hipError_t grawa_launch_rows_step(float *x, int64_t ldx, const void *g, int64_t ldg, grawa_dtype_t dt, float lr,
-                                  const float *center, float w, const GrawaTile *tiles, int tile_elems,
-                                  int64_t n_tiles, int K, int64_t P, double *partials, hipStream_t s);
+hipError_t grawa_launch_row_step(float *x, int64_t ldx, const void *g, int64_t ldg, grawa_dtype_t dt, float lr,
+                                 const float *center, float w, int K, int64_t P, const GrawaTile *tiles,
+                                 const int32_t *block_tile0, int64_t n_tiles, double *partials, hipStream_t s);
 hipError_t grawa_launch_finalize_model(const grawa_plan *p, grawa_norm_mode_t mode, float *beta_user,
                                        hipStream_t s);
 hipError_t grawa_launch_center_pull(const grawa_plan *p, float *x, int64_t ldx, const float *beta,
@@ -74,13 +74,8 @@ hipError_t grawa_launch_center_pull(const grawa_plan *p, float *x, int64_t ldx, 
 hipError_t grawa_launch_nesterov(float *x, int64_t ldx, const void *g, int64_t ldg, grawa_dtype_t dt,
                                  float *buf, int64_t ldb, int K, int64_t P, float lr, float momentum,
                                  float wd, hipStream_t s);
-hipError_t grawa_launch_row_step_scored(float *x, int64_t ldx, const void *g, int64_t ldg, grawa_dtype_t dt,
-                                        float lr, const GrawaTile *tiles, const int32_t *block_tile0,
-                                        int64_t n_tiles, int K, int64_t P, double *partials, hipStream_t s);
 hipError_t grawa_launch_center_weights(const grawa_plan *p, const float *loss, float *beta_user,
                                        int *leader_out, hipStream_t s);
-hipError_t grawa_launch_local_sgd(float *x, int64_t ldx, const void *g, int64_t ldg,
-                                  grawa_dtype_t dt, int K, int64_t P, float lr, hipStream_t s);
 hipError_t grawa_launch_stream_copy(void *dst, const void *src, int64_t nbytes, hipStream_t s);
 
 #endif

@@ -178,9 +178,9 @@ def summarize_phases(base: str, cfg: int, out_dir: str):
     for name, c in ph["calls"].items():
         lines.append("| %s | %.4f | %d | %.0f | %.1f |" % (name, c["ms"], c["bytes"], c["GBps"], 100 * c["frac_of_peak"]))
     lines += ["", "## --kernel-trace --stats (library kernels only)", "",
-              "k_rows_step<K, exact, grad type, streaming, PROX, SCORE, waves>: SGD (+ proximity step) (+ per-tile "
-              "gradient sums of squares).  k_center_pull here serves the Local-GRAWA communication and the EASGD and "
-              "LSGD phases together.", "",
+              "k_row_step<grad type, V, U, streaming, PROX, SCORE>: SGD (+ proximity step) (+ per-tile gradient "
+              "sums of squares), one worker per block.  k_center_pull here serves the Local-GRAWA communication "
+              "and the EASGD and LSGD phases together.", "",
               "| kernel | calls | avg us | min us | max us | algorithmic bytes/launch | GB/s at avg | % of 8 TB/s |",
               "|---|---|---|---|---|---|---|---|"]
     for name, calls, avg, mn, mx, _pct in stats:
@@ -189,11 +189,9 @@ def summarize_phases(base: str, cfg: int, out_dir: str):
             continue
         ta = template_args(name)
         ab = None
-        if base_name == "k_local_sgd":
-            ab = K * P * (8 + gb)
-        elif base_name == "k_nesterov":
+        if base_name == "k_nesterov":
             ab = K * P * (16 + gb)
-        elif base_name == "k_rows_step":
+        elif base_name == "k_row_step":
             ab = K * P * (8 + gb) + (4 * P if len(ta) > 4 and ta[4] == "true" else 0)
         elif base_name == "k_center_pull":
             ab = K * P * 8

@@ -106,6 +106,7 @@ def test_local_sgd_argument_checks(L):
     assert f(a, 16, a, 20, 1, 2, 16, 0.1, z) == grawa.ERR_ALIGNMENT        # bf16 ldg*2 not a multiple of 16
     assert f(a, 16, a, 16, 7, 2, 16, 0.1, z) == grawa.ERR_UNSUPPORTED      # unknown dtype
     assert f(a, 16, a, 16, 0, 2, 16, float("nan"), z) == grawa.ERR_INVALID_ARG
+    assert f(a, 16, a, 16, 0, 65536, 16, 0.1, z) == grawa.ERR_UNSUPPORTED   # more workers than grid rows
     assert f(a, 16, a, 16, 0, 2, 16, float("inf"), z) == grawa.ERR_INVALID_ARG
 
 

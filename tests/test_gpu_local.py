@@ -28,7 +28,7 @@ def scale_of(xh, P, grads, lr, center=None):
     return s
 
 
-@pytest.mark.parametrize("K", [1, 3, 4, 8, 16, 17, 24, 32, 33, 64])
+@pytest.mark.parametrize("K", [1, 3, 4, 8, 16, 17, 32, 33, 64, 130])
 @pytest.mark.parametrize("dtype", ["f32", "bf16"])
 def test_local_sgd_prox(K, dtype):
     for ld_pad in (0, 8):
@@ -56,10 +56,6 @@ def test_local_sgd_prox_limits():
         with pytest.raises(grawa.GrawaError) as e:
             grawa.local_sgd_prox(x[:, :100], g[:, :100], 0.1, cen, mu, tau)
         assert e.value.status == grawa.ERR_INVALID_ARG
-    w65, x65, g65 = W.make_small(6, 65, [100], device=DEV)
-    with pytest.raises(grawa.GrawaError) as e:
-        grawa.local_sgd_prox(x65[:, :100], g65[:, :100], 0.1, cen, 0.1, 4.0)
-    assert e.value.status == grawa.ERR_UNSUPPORTED
     torch.cuda.synchronize()
     assert torch.equal(x, x0)
     # mu = 0 is the plain SGD step; mu = tau lands exactly on the stored center
