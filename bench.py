@@ -200,13 +200,12 @@ def time_phases(torch, grawa, W, idx, steps, warmup):
             plan.local_lgrawa_update(xv, w.lam)
 
         run("local_sgd", step, lambda: grawa.local_sgd(xv, gv, lr))
-        if K <= 64:
-            run("local_sgd_prox", step + 4 * P, lambda: grawa.local_sgd_prox(xv, gv, lr, cen, 0.05, 16.0))
-            run("local_step_scored", step, lambda: plan.local_step_scored(xv, gv, lr, 0.9))
-            run("local_step_scored_prox", step + 4 * P,
-                lambda: plan.local_step_scored(xv, gv, lr, 0.9, center=cen, mu=0.05, tau=16.0))
-            plan.local_scores_reset()
-            run("local_round_1step_lgrawa", step + K * P * 8, local_round)
+        run("local_sgd_prox", step + 4 * P, lambda: grawa.local_sgd_prox(xv, gv, lr, cen, 0.05, 16.0))
+        run("local_step_scored", step, lambda: plan.local_step_scored(xv, gv, lr, 0.9))
+        run("local_step_scored_prox", step + 4 * P,
+            lambda: plan.local_step_scored(xv, gv, lr, 0.9, center=cen, mu=0.05, tau=16.0))
+        plan.local_scores_reset()
+        run("local_round_1step_lgrawa", step + K * P * 8, local_round)
         run("easgd_update", K * P * 8 + 8 * P, lambda: plan.easgd_update(xv, w.lam, 0.5, cen))
         run("lsgd_update", K * P * 8, lambda: plan.lsgd_update(xv, losses, w.lam))
     del cen

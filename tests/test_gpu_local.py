@@ -70,9 +70,10 @@ def test_local_sgd_prox_limits():
 @pytest.mark.parametrize("K,dtype,steps,prox", [(4, "f32", 1, False), (4, "f32", 3, True), (8, "bf16", 4, True),
                                                (16, "f32", 2, False), (32, "f32", 2, True), (5, "bf16", 5, False),
                                                (40, "f32", 2, True), (70, "f32", 2, False), (3, "bf16", 2, False),
-                                               (33, "bf16", 1, False)])
+                                               (33, "bf16", 1, False), (1024, "f32", 1, False),
+                                               (256, "bf16", 1, True)])
 def test_local_round(policy, K, dtype, steps, prox):
-    sizes = RAGGED if K <= 16 else RAGGED[:8]
+    sizes = RAGGED if K <= 16 else (RAGGED[:8] if K <= 70 else [300, 5, 1000, 1, 257])
     ld_pad = 8 if K in (3, 5, 70) else 0                 # rows that are 16-byte but not line aligned
     w, x, g0 = W.make_small(400 + K, K, sizes, grad_dtype=dtype, ld_pad=ld_pad, device=DEV)
     P, L = w.P, w.L

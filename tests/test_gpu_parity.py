@@ -96,6 +96,15 @@ def test_worker_counts_ragged(K, dtype, ld_pad):
     run_variant(w, x, g, "flat", 0.7, fused=True, lr=0.05, want_center=False, want_weights=False)
 
 
+@pytest.mark.parametrize("K", [256, 1024])            # 1024 = GRAWA_MAX_WORKERS
+def test_many_workers(K):
+    w, x, g = W.make_small(900 + K, K, [300, 5, 1000, 1, 257], device=DEV)
+    say("many workers K=%d P=%d" % (K, w.P))
+    run_variant(w, x, g, "mgrawa", 0.3)
+    run_variant(w, x, g, "lgrawa", 0.3)
+    run_variant(w, x, g, "lgrawa", 0.25, fused=True, lr=0.1)
+
+
 @pytest.mark.parametrize("sizes", [[1], [2], [3], [4], [5], [7, 1], [1, 1, 1, 1, 1], [8192], [8193], [8191, 1, 8192],
                                    [16384, 3], SMALL])
 def test_tiny_and_boundary_layouts(sizes):
