@@ -64,11 +64,14 @@ def window_reference(w, beta, x0, g, i0, i1, lam, fused, lr):
 
 
 def run_full(cfg_index, variant, full_compare):
-    w = W.config(cfg_index)
+    run_workload(W.config(cfg_index), variant, full_compare, cfg_index)
+
+
+def run_workload(w, variant, full_compare, cfg_index):
     P, K = w.P, w.K
     fused = w.fused_sgd
     lr = w.lr if fused else 0.0
-    say("config %d %s K=%d L=%d P=%d grads=%s fused_sgd=%s" % (cfg_index, variant, K, w.L, P, w.grad_dtype, fused))
+    say("%s (%d) %s K=%d L=%d P=%d grads=%s fused_sgd=%s" % (w.name, cfg_index, variant, K, w.L, P, w.grad_dtype, fused))
     x, g = W.make_inputs(w, device=DEV)
     x0 = x.clone()
     per_layer = variant == "lgrawa"
@@ -278,3 +281,37 @@ def test_full_size_nesterov_easgd_lsgd(cfg_index):
         assert_params_close(x2[:, i0:i1].cpu().numpy(), rx, off, TIGHT, "lsgd x [%d,%d)" % (i0, i1), operand_scale(xs))
     assert torch.equal(x2[want_lead], x0[want_lead])          # the leader does not move
     assert torch.equal(x[:, P:], x0[:, P:]) and torch.equal(cen[P:], cen0[P:])
+
+
+def test_more_than_2_31_columns():
+    # 64-bit indexing: a row longer than 2^31 elements, a layer boundary three columns below 2^31, a row
+    # length that is not a multiple of 4; fused LGRAWA update with bf16 gradients (x 17 GB, g 8.6 GB).
+    free, _ = torch.cuda.mem_get_info()
+    if free < 150 * (1 << 30):
+        pytest.skip("needs 150 GB of free device memory")
+    w = W.Workload("wide_K2", 2, [2 ** 31 - 3, 8200], grad_dtype="bf16", lam=0.3, lr=0.1, fused_sgd=True,
+                   variants=("lgrawa",), seed=(2, 1))
+    run_workload(w, "lgrawa", False, 99)
+    # the row-by-row local steps on the same shape: scored SGD + proximity step, then the communication
+    P, K = w.P, w.K
+    x, g = W.make_inputs(w, device=DEV)
+    x0 = x.clone()
+    cen = 0.05 * torch.randn(W.round_up(P, 4), device=DEV, generator=torch.Generator(device=DEV).manual_seed(3))
+    est = torch.empty((K, w.L), device=DEV)
+    lr, gamma, mu, tau = 0.05, 0.9, 0.05, 16.0
+    with grawa.Plan(K, P, w.offsets) as plan:
+        plan.local_step_scored(x[:, :P], g[:, :P], lr, gamma, center=cen, mu=mu, tau=tau)
+        plan.local_lgrawa_update(x[:, :P], 0.0, est_out=est)       # lambda = 0: x keeps the local step's result
+        torch.cuda.synchronize()
+    scores = orc.LocalScores(K, w.L, gamma)
+    scores.step(W.to_numpy_grads(g), w.offsets)
+    assert_table_close(est.cpu().numpy(), scores.g_est, TIGHT, "g_est beyond 2^31")
+    for i0 in (0, 2 ** 31 - 2051, 2 ** 31 - 3, P - WINDOW):
+        i1 = min(P, i0 + WINDOW)
+        xs = np.ascontiguousarray(x0[:, i0:i1].cpu().numpy())
+        gs = W.to_numpy_grads(g[:, i0:i1].contiguous())
+        ch = cen[i0:i1].cpu().numpy().astype(np.float64)
+        ref = orc.local_sgd(xs, gs, lr, prox_center=ch, mu=mu, tau=tau)
+        sc = np.maximum(operand_scale(xs, gs, lr), np.abs(ch))
+        assert_params_close(x[:, i0:i1].cpu().numpy(), ref, np.array([0, i1 - i0]), TIGHT, "local step [%d,%d)" % (i0, i1), sc)
+    assert torch.equal(x[:, P:], x0[:, P:])
