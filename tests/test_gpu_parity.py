@@ -182,6 +182,40 @@ def test_zero_norm_rule_on_device():
     np.testing.assert_array_equal(b[:, 1], np.float32([0, 0, 1, 0]))
 
 
+def test_non_finite_scores():
+    # an infinite score gets weight 0 (the same limit as the zero rule), a NaN score spreads to its group
+    w, x, g = W.make_small(32, 4, [40, 9000, 17, 64], device=DEV)
+    say("non-finite scores")
+    off, P = w.offsets, w.P
+    g[1, off[1] + 5] = float("inf")
+    g[3, off[3] + 1] = float("nan")
+    xh, gh = host(x, g)
+    ref = orc.lgrawa_update(xh, gh, off, 0.5)
+    assert ref["beta"][1, 1] == 0.0 and np.all(np.isnan(ref["beta"][:, 3])) and np.all(np.isfinite(ref["beta"][:, :3]))
+    wts = torch.empty((4, 4), device=DEV)
+    xg = x.clone()
+    with grawa.Plan(4, P, off) as plan:
+        plan.lgrawa_update(xg[:, :P], g[:, :P], 0.5, weights_out=wts)
+        torch.cuda.synchronize()
+        got_b = wts.cpu().numpy()
+        np.testing.assert_array_equal(np.isnan(got_b), np.isnan(ref["beta"]))
+        assert_table_close(got_b[:, :3], ref["beta"][:, :3], TIGHT, "beta with an infinite score")
+        got = xg.cpu().numpy()
+        fin = int(off[3])
+        assert_params_close(got[:, :fin], ref["x"][:, :fin], off[:4], TIGHT, "x, finite layers", operand_scale(xh[:, :fin]))
+        assert np.all(np.isnan(got[:, fin:P])) and np.all(np.isnan(ref["x"][:, fin:]))
+        # model level: the worker with the infinite score gets nothing, the NaN takes everything down
+        wm = torch.empty(4, device=DEV)
+        g[3, off[3] + 1] = 1.0
+        xg = x.clone()
+        plan.mgrawa_update(xg[:, :P], g[:, :P], 0.5, weights_out=wm)
+        torch.cuda.synchronize()
+        refm = orc.mgrawa_update(xh, W.to_numpy_grads(g), off, 0.5)
+        assert refm["beta"][1] == 0.0
+        assert_table_close(wm.cpu().numpy(), refm["beta"], TIGHT, "model-level beta with an infinite score")
+        assert_params_close(xg.cpu().numpy()[:, :P], refm["x"], off, TIGHT, "x, infinite score", operand_scale(xh[:, :P]))
+
+
 def test_exact_special_cases():
     say("K=1 / lambda=0 / lambda=1")
     # K = 1: the worker is left bit-for-bit unchanged
