@@ -133,7 +133,8 @@ grawa_status_t grawa_center_pull(grawa_plan_t *plan, float *x, int64_t ldx, cons
 
 /*
  * Local SGD step of Algorithms 1 and 2: x_k <- x_k - lr * g_k for every worker.
- * Needs no plan.  lr must be finite.
+ * Needs no plan.  lr must be finite.  K <= 65535 and P < 2^32 (UNSUPPORTED
+ * beyond); the same limits hold for the other plan-less local steps below.
  */
 grawa_status_t grawa_local_sgd(float *x, int64_t ldx, const void *g, int64_t ldg,
                                grawa_dtype_t g_dtype, int K, int64_t P, float lr, void *stream);
