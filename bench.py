@@ -324,7 +324,7 @@ def measured_traffic(workload, variant):
 def main():
     a = parse()
     if a.gpus != 1:
-        print("bench.py: this build runs the GRAWA update on ONE GPU (all K workers of a configuration "
+        print("bench.py: the GRAWA update runs on ONE GPU (all K workers of a configuration "
               "live on it); --gpus %d is not supported." % a.gpus, file=sys.stderr)
         sys.exit(2)
     import torch

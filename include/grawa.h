@@ -48,7 +48,7 @@ typedef enum {
     GRAWA_ERR_INVALID_ARG = 1, /* null pointer, bad size, non-monotone offsets, lambda outside [0,1], non-finite scalar */
     GRAWA_ERR_ALIGNMENT = 2,   /* base pointer or leading dimension not 16-byte aligned */
     GRAWA_ERR_WORKSPACE = 3,   /* the plan could not get its device workspace */
-    GRAWA_ERR_UNSUPPORTED = 4, /* a size or dtype this build does not handle (K > GRAWA_MAX_WORKERS, ...) */
+    GRAWA_ERR_UNSUPPORTED = 4, /* a size or dtype the library does not handle (K > GRAWA_MAX_WORKERS, ...) */
     GRAWA_ERR_HIP = 5          /* a HIP runtime call or a kernel launch failed */
 } grawa_status_t;
 

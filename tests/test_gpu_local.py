@@ -134,7 +134,7 @@ def test_two_rounds_and_reset():
         plan.local_step_scored(xg[:, :P], g2[:, :P], 0.1, 0.7)
         plan.local_mgrawa_update(xg[:, :P], 0.4)
         torch.cuda.synchronize()
-    # reference: SGD with g (estimate discarded), then round 1 = [g2], round 2 = [g, g2]
+    # reference: SGD with g (estimate discarded), then a first communication round with [g2] and a second with [g, g2]
     x1 = orc.local_sgd(xh, gh, 0.1, P=P).astype(np.float32)          # rounding to fp32 here mirrors the stored state
     r1 = orc.local_grawa_round(np.ascontiguousarray(x1), [gh2], w.offsets, 0.1, 0.2, 0.5, "lgrawa")
     x2 = r1["x"].astype(np.float32)
