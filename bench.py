@@ -116,9 +116,12 @@ def time_config(torch, grawa, W, idx, variant, steps, warmup):
             print("bench.py: graph replay skipped: %s" % e, file=sys.stderr)
         # the same steps again with start/stop events attached to the two big kernels
         plan.profile(True)
+        torch.cuda.synchronize()
+        e0 = time.perf_counter()
         for _ in range(steps):
             call_update(plan, w, x, g, variant)
         torch.cuda.synchronize()
+        ms_events = (time.perf_counter() - e0) * 1e3 / steps
         prof = plan.profile_read()
         per_call = [plan.profile_read_call(i) for i in range(prof["calls"])]
         plan.profile(False)
@@ -138,7 +141,7 @@ def time_config(torch, grawa, W, idx, variant, steps, warmup):
         "pull_kernel_ms": pull_ms, "pull_kernel_GBps": pull_bytes / (pull_ms * 1e-3) / 1e9 if pull_ms > 0 else None,
         "pull_kernel_bytes": pull_bytes, "tile_elems": info["tile_elems"], "n_tiles": info["n_tiles"],
         # per update, first kernel start to last kernel end on the device (the event pass)
-        "graph_replay_ms_per_step": graph_ms,
+        "graph_replay_ms_per_step": graph_ms, "ms_per_step_event_pass": ms_events,
         "device_ms": spread([c["span_ms"] for c in per_call]),
         "pull_kernel_ms_spread": spread([c["pull_ms"] for c in per_call]),
     }
@@ -363,6 +366,7 @@ def main():
                    "tile_elems": stats["tile_elems"]},
         "frac_of_hbm_peak": stats["frac_of_peak"], "updates_per_s": stats["updates_per_s"],
         "device_ms_per_update": stats["device_ms"], "graph_replay_ms_per_step": stats["graph_replay_ms_per_step"],
+        "ms_per_step_event_pass": stats["ms_per_step_event_pass"],
         "roofline": roofline,
     }
     out["copy_kernel"] = copy_ceiling(torch, grawa)
@@ -373,7 +377,7 @@ def main():
             if i == a.config:
                 sweep.append({k: stats[k] for k in ("workload", "variant", "ms_per_step", "updates_per_s", "GBps",
                                                      "frac_of_peak", "pull_kernel_GBps", "norm_kernel_GBps",
-                                                     "graph_replay_ms_per_step")})
+                                                     "graph_replay_ms_per_step", "ms_per_step_event_pass")})
                 continue
             for var in W.config(i).variants:
                 s, x, g, _ = time_config(torch, grawa, W, i, var, a.steps, a.warmup)
@@ -381,7 +385,7 @@ def main():
                 torch.cuda.empty_cache()
                 sweep.append({k: s[k] for k in ("workload", "variant", "ms_per_step", "updates_per_s", "GBps",
                                                  "frac_of_peak", "pull_kernel_GBps", "norm_kernel_GBps",
-                                                 "graph_replay_ms_per_step")})
+                                                 "graph_replay_ms_per_step", "ms_per_step_event_pass")})
         out["all_configs"] = sweep
     if not a.no_phases and not a.no_sweep:
         out["phases"] = time_phases(torch, grawa, W, a.config, a.steps, a.warmup)
