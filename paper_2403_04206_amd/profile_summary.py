@@ -8,6 +8,7 @@ Expected input, one directory per run (any parent folder):
     <dir>/prof_cfg<N>_write   same command with  --pmc WRITE_SIZE
     <dir>/prof_cfg<N>_phases  (optional) --kernel-trace --stats of
                                     python3 bench.py --config <N> --only-phases
+    <dir>/prof_cfg<N>_phases_fetch, _phases_write  (optional) the same with --pmc FETCH_SIZE / WRITE_SIZE
 
 FETCH_SIZE / WRITE_SIZE are reported in KiB per dispatch.  Each is scaled by what the same
 counter reads, in the same run, for the library's plain copy kernel (bench.py launches it over
@@ -151,7 +152,7 @@ def summarize(base: str, cfg: int, out_dir: str):
 
 
 def template_args(name: str):
-    if "<" not in name:
+    if "<" not in name or ">" not in name or name.rindex(">") < name.index("<"):
         return []
     return [a.strip() for a in name[name.index("<") + 1:name.rindex(">")].split(",")]
 
@@ -199,6 +200,29 @@ def summarize_phases(base: str, cfg: int, out_dir: str):
         frac = "%.1f" % (100 * ab / avg / 8000.0) if ab else "-"
         lines.append("| %s | %d | %.1f | %.1f | %.1f | %s | %s | %s |" %
                      (name, calls, avg / 1e3, mn / 1e3, mx / 1e3, ab if ab else "-", gbps, frac))
+    fdir, wdir = run_dir + "_fetch", run_dir + "_write"
+    if os.path.isdir(fdir) and os.path.isdir(wdir):
+        fetch, write = read_counters(fdir, "FETCH_SIZE"), read_counters(wdir, "WRITE_SIZE")
+        f_scale = COPY_BYTES / (fetch["k_stream_copy"][0] * 1024.0)
+        w_scale = COPY_BYTES / (write["k_stream_copy"][0] * 1024.0)
+        lines += ["", "## HBM traffic per launch (--pmc FETCH_SIZE, --pmc WRITE_SIZE of the same command)", "",
+                  "Scaled by what the counters read for the plain copy kernel in the same run (scales %.4f and %.4f). "
+                  "The proximity center is read by every worker's blocks but fetched from HBM about once: the "
+                  "launch order keeps it in cache." % (f_scale, w_scale), "",
+                  "| kernel | scaled read bytes | scaled written bytes | total | algorithmic bytes | total / algorithmic |",
+                  "|---|---|---|---|---|---|"]
+        for name in sorted(fetch):
+            base_name = name.split("<")[0]
+            ta = template_args(name)
+            if base_name == "k_nesterov":
+                ab = K * P * (16 + gb)
+            elif base_name == "k_row_step":
+                ab = K * P * (8 + gb) + (4 * P if len(ta) > 4 and ta[4] == "true" else 0)
+            else:
+                continue
+            fr = fetch[name][0] * 1024 * f_scale
+            wr = write.get(name, (0.0, 0))[0] * 1024 * w_scale
+            lines.append("| %s | %.4g | %.4g | %.4g | %d | %.4f |" % (name, fr, wr, fr + wr, ab, (fr + wr) / ab))
     lines.append("")
     out = os.path.join(out_dir, "phase_kernels_%s.md" % ph["workload"])
     with open(out, "w") as f:
