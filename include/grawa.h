@@ -24,6 +24,12 @@
  *    Calls enqueue their kernels on it and return without synchronising; two
  *    calls that use the same plan must be ordered on one stream (the plan's
  *    workspace is shared).
+ *  - Calls that take a plan run on the device the plan was created on (they
+ *    switch to it and back); calls without a plan run on the caller's current
+ *    device, which must own the buffers and the stream.
+ *  - For full speed give x and g row pitches that are multiples of 1 KiB
+ *    (256 fp32 elements): rows then start on cache-line boundaries and the
+ *    kernels use streaming accesses.  Any legal pitch gives the same results.
  *  - Base pointers of x, g, center_out must be 16-byte aligned and ldx*4,
  *    ldg*sizeof(g element) must be multiples of 16; otherwise
  *    GRAWA_ERR_ALIGNMENT.  Layer offsets may be arbitrary.
