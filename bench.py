@@ -371,6 +371,7 @@ def main():
         "roofline": roofline,
     }
     out["copy_kernel"] = copy_ceiling(torch, grawa)
+    out["frac_of_copy_kernel"] = stats["GBps"] / out["copy_kernel"]["GBps"]     # against this machine's own copy rate
     torch.cuda.empty_cache()
     if not a.no_sweep:
         sweep = []
