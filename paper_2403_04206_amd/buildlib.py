@@ -79,5 +79,20 @@ def build(force: bool = True, verbose: bool = False) -> str:
     return LIB
 
 
+def build_c_client(src: str, out: str) -> str:
+    """Compile a plain C99 program that calls the library through include/grawa.h (gcc, linked against
+    libgrawa.so and the HIP runtime; the library is found relative to the program's own location)."""
+    rocm = os.environ.get("ROCM_PATH", "/opt/rocm")
+    os.makedirs(os.path.dirname(out), exist_ok=True)
+    cmd = ["gcc", "-std=c99", "-O1", "-Wall", "-Wextra", "-D__HIP_PLATFORM_AMD__", "-I", os.path.join(ROOT, "include"),
+           "-I", os.path.join(rocm, "include"), src, "-o", out, "-L", PKG, "-l:libgrawa.so",
+           "-L", os.path.join(rocm, "lib"), "-lamdhip64", "-Wl,-rpath," + os.path.relpath(PKG, os.path.dirname(out)).join(
+               ["$ORIGIN/", ""]), "-Wl,-rpath," + os.path.join(rocm, "lib")]
+    res = subprocess.run(cmd, stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True)
+    if res.returncode != 0:
+        raise RuntimeError("gcc failed:\n" + res.stdout)
+    return out
+
+
 if __name__ == "__main__":
     print(build(force=True, verbose=True))

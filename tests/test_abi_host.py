@@ -144,3 +144,20 @@ def test_bench_refuses_more_than_one_gpu():
                          timeout=120)
     assert res.returncode != 0
     assert "ONE GPU" in res.stderr and res.stdout.strip() == ""
+
+
+def test_header_is_plain_c99_and_the_c_client_builds(tmp_path):
+    # The boundary is a C ABI: the header must compile as C (not only as C++), and a C99 program that
+    # uses it must link against the library (running it needs a GPU and is a GPU test).
+    import shutil
+    import subprocess
+    gcc = shutil.which("gcc")
+    if gcc is None:
+        pytest.skip("no gcc")
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    hdr = os.path.join(root, "include", "grawa.h")
+    res = subprocess.run([gcc, "-std=c99", "-Wall", "-Wextra", "-pedantic", "-Werror", "-fsyntax-only", "-x", "c", hdr],
+                         capture_output=True, text=True)
+    assert res.returncode == 0, res.stderr
+    out = buildlib.build_c_client(os.path.join(root, "tests", "c_abi_client.c"), str(tmp_path / "client"))
+    assert os.path.exists(out)
