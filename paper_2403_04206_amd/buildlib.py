@@ -20,7 +20,7 @@ HEADERS = [os.path.join(CSRC, "grawa_internal.h"), os.path.join(CSRC, "grawa_dev
 HIPCC_FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-x", "hip",
     "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
-    "-Wall", "-Wno-unused-command-line-argument",
+    "-Wall", "-Wextra", "-Wno-unused-command-line-argument",
 ]
 
 

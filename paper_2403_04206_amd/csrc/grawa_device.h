@@ -193,14 +193,6 @@ template <int V> __device__ __forceinline__ void vec_set(typename FloatVec<V>::T
     else v[c] = f;
 }
 
-// Waves per SIMD the center+pull kernel is capped at, from a sweep of this kernel over K and
-// the cap on the part (best throughput at roughly 32-48 row loads in flight per SIMD).
-constexpr int grawa_waves_for(int k, bool sgd)
-{
-    if (sgd) return k <= 2 ? 8 : k == 3 ? 6 : k <= 5 ? 5 : k <= 7 ? 4 : k <= 11 ? 3 : 2;
-    return k <= 4 ? 8 : k == 5 ? 6 : k <= 7 ? 5 : k <= 10 ? 4 : k <= 20 ? 3 : k <= 28 ? 2 : 1;
-}
-
 #define GRAWA_STREAMING_MIN_BYTES ((int64_t)512 << 20)
 
 // Streaming accesses are used only when no cache line is shared between two rows or written

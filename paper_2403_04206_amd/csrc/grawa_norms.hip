@@ -175,7 +175,7 @@ __global__ __launch_bounds__(GRAWA_FIN_BLOCK) void k_finalize_layers(
                                  share * GRAWA_WAVE);
         if (lane == 0) sw[wave] = s;
         __syncthreads();
-        if (threadIdx.x < K) {
+        if ((int)threadIdx.x < K) {
             double tot = 0.0;
             for (int j = 0; j < share; ++j) tot += sw[threadIdx.x + j * K];
             sA[threadIdx.x] = tot;

@@ -128,6 +128,14 @@ __global__ __launch_bounds__(GRAWA_CELL) void k_center_pull_any(
 // launchers
 // ---------------------------------------------------------------------------------
 
+// Waves per SIMD the center+pull kernel is capped at, from a sweep of this kernel over K and
+// the cap on the part (best throughput at roughly 32-48 row loads in flight per SIMD).
+constexpr int grawa_waves_for(int k, bool sgd)
+{
+    if (sgd) return k <= 2 ? 8 : k == 3 ? 6 : k <= 5 ? 5 : k <= 7 ? 4 : k <= 11 ? 3 : 2;
+    return k <= 4 ? 8 : k == 5 ? 6 : k <= 7 ? 5 : k <= 10 ? 4 : k <= 20 ? 3 : k <= 28 ? 2 : 1;
+}
+
 template <int KT, bool EXACT, bool SGD, typename GT, bool NT>
 static void launch_cp(const grawa_plan *p, float *x, int64_t ldx, const void *g, int64_t ldg, float lr,
                       const float *beta, int per_layer, float lambda, float *center_out, float rho, int moving,
