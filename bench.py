@@ -306,10 +306,10 @@ def cpu_baseline(torch, W, w, variant, target_seconds):
 
 def measured_traffic(workload, variant):
     """HBM bytes per launch of the center+pull kernel from the committed rocprofv3 counter runs
-    (profiles/traffic.json), or None when there is no entry for this workload or the library
+    (profiles/traffic.txt), or None when there is no entry for this workload or the library
     sources have changed since the counters were taken."""
     from paper_2403_04206_amd import profile_summary
-    path = os.path.join(ROOT, "profiles", "traffic.json")
+    path = os.path.join(ROOT, "profiles", "traffic.txt")
     try:
         with open(path) as f:
             tj = json.load(f)

@@ -1,5 +1,5 @@
 """Turn rocprofv3 CSV output of bench.py runs into the short text summaries kept under
-profiles/ and into profiles/traffic.json (HBM bytes per launch of the update kernels).
+profiles/ and into profiles/traffic.txt (HBM bytes per launch of the update kernels).
 
 Expected input, one directory per run (any parent folder):
     <dir>/prof_cfg<N>_stats   from  rocprofv3 --kernel-trace --stats -d <that dir> --output-format csv
@@ -242,7 +242,7 @@ def main(argv):
         print("wrote summary for", name)
         if summarize_phases(base, c, out_dir):
             print("wrote phase summary for", name)
-    with open(os.path.join(out_dir, "traffic.json"), "w") as f:
+    with open(os.path.join(out_dir, "traffic.txt"), "w") as f:
         json.dump(tj, f, indent=1)
 
 
