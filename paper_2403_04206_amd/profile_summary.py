@@ -101,6 +101,9 @@ def summarize(base: str, cfg: int, out_dir: str):
         lines.append("    rocprofv3 %s -d <out> --output-format csv -- python3 $R/bench.py --config %d --no-sweep "
                      "--no-cpu-baseline" % (args, cfg))
     lines.append("")
+    lines.append("The CSV output of the three runs was turned into this file by "
+                 "`python -m paper_2403_04206_amd.profile_summary <dir holding the three output folders> %d`." % cfg)
+    lines.append("")
     lines.append("bench.py line of the --kernel-trace run: value %.0f GB/s (%.1f%% of 8 TB/s), %.4f ms/update, "
                  "%.0f updates/s; center+pull kernel from HIP events %.4f ms/launch." %
                  (bl["value"], 100 * bl["frac_of_hbm_peak"], bl["ms_per_step"], bl["updates_per_s"],
@@ -174,6 +177,8 @@ def summarize_phases(base: str, cfg: int, out_dir: str):
              "Command (run from /tmp with TMPDIR=/tmp, repository root = $R):", "",
              "    rocprofv3 --kernel-trace --stats -d <out> --output-format csv -- python3 $R/bench.py --config %d "
              "--only-phases" % cfg, "",
+             "(and the same command under `--pmc FETCH_SIZE` and `--pmc WRITE_SIZE` for the traffic table); turned "
+             "into this file by `python -m paper_2403_04206_amd.profile_summary <dir> %d`." % cfg, "",
              "## Calls, from stream events inside bench.py (minimum-traffic byte model of each call)", "",
              "| call | ms | bytes | GB/s | % of 8 TB/s |", "|---|---|---|---|---|"]
     for name, c in ph["calls"].items():
