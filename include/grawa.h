@@ -95,8 +95,13 @@ grawa_status_t grawa_plan_destroy(grawa_plan_t *plan);
 /*
  * Gradient-norm scores, Sec. 5.2 eq. (5)-(6): norms_out[k][l] = ||g_k restricted
  * to layer l||_F, the Frobenius norm of worker k's accumulated gradient in layer
- * l.  Sums of squares are accumulated in fp32 per thread over at most 32
- * elements and in fp64 from there on.  norms_out: device float [K][L].
+ * l.  Every gradient value is widened to fp64 before it is squared and all
+ * sums are fp64 in a fixed order: squares are exact, nothing underflows or
+ * overflows for any magnitude the gradient type can hold, and results are
+ * bit-reproducible.  The tables handed back (norms, weights, estimates) are
+ * float32: an entry whose exact value lies outside the float32 range is
+ * rounded to 0 or +inf there, while the weights used inside the update are
+ * formed from the fp64 scores.  norms_out: device float [K][L].
  */
 grawa_status_t grawa_grad_norms(grawa_plan_t *plan, const void *g, int64_t ldg,
                                 grawa_dtype_t g_dtype, float *norms_out, void *stream);

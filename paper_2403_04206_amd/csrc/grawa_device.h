@@ -95,6 +95,13 @@ template <bool NT, typename T> __device__ __forceinline__ void st_lane(uint64_t 
     else *p = v;
 }
 
+// acc + v^2 with the value widened first: one fp64 fused multiply-add.
+__device__ __forceinline__ double sq_add(float v, double acc)
+{
+    const double d = (double)v;
+    return fma(d, d, acc);
+}
+
 // Gradient element access.  VEC8 = elements per 8-byte load (norm pass).
 template <typename GT> struct Grad;
 
@@ -105,16 +112,18 @@ template <> struct Grad<float> {
     {
         return ld_lane<NT, float>(base, off);
     }
-    // 8 bytes (2 floats) at p, 8-byte aligned, streaming load; and their squares added to acc
+    // 8 bytes (2 floats) at p, 8-byte aligned, streaming load; and their squares added to acc.
+    // The square of a widened fp32 (or bf16) value is exact in fp64, so no gradient magnitude
+    // that the input type can hold underflows or overflows here.
     typedef v2f Vec8;
     static __device__ __forceinline__ Vec8 load8(const float *p)
     {
         return __builtin_nontemporal_load(reinterpret_cast<const v2f *>(p));
     }
-    static __device__ __forceinline__ float sumsq8(Vec8 q, float acc)
+    static __device__ __forceinline__ double sumsq8(Vec8 q, double acc)
     {
-        acc = fmaf(q.x, q.x, acc);
-        acc = fmaf(q.y, q.y, acc);
+        acc = sq_add(q.x, acc);
+        acc = sq_add(q.y, acc);
         return acc;
     }
 };
@@ -132,13 +141,12 @@ template <> struct Grad<uint16_t> { // bfloat16 bit patterns
     {
         return __builtin_nontemporal_load(reinterpret_cast<const v2u *>(p));
     }
-    static __device__ __forceinline__ float sumsq8(Vec8 q, float acc)
+    static __device__ __forceinline__ double sumsq8(Vec8 q, double acc)
     {
-        float a;
-        a = bf16_lo(q.x); acc = fmaf(a, a, acc);
-        a = bf16_hi(q.x); acc = fmaf(a, a, acc);
-        a = bf16_lo(q.y); acc = fmaf(a, a, acc);
-        a = bf16_hi(q.y); acc = fmaf(a, a, acc);
+        acc = sq_add(bf16_lo(q.x), acc);
+        acc = sq_add(bf16_hi(q.x), acc);
+        acc = sq_add(bf16_lo(q.y), acc);
+        acc = sq_add(bf16_hi(q.y), acc);
         return acc;
     }
 };

@@ -99,25 +99,25 @@ __global__ __launch_bounds__(GRAWA_CELL) void k_row_step(float *__restrict__ x, 
     if (!SCORE) return;
     double *out = partials + (int64_t)k * n_tiles;
     if (r1 - r0 == 1) { // the usual case: the whole block lies in one tile
-        float acc = 0.f;
+        double acc = 0.0; // squares and sums in fp64: exact squares at any gradient magnitude
 #pragma unroll
         for (int u = 0; u < U; ++u)
 #pragma unroll
-            for (int e = 0; e < V; ++e) acc = fmaf(gf[u][e], gf[u][e], acc);
-        const double tot = block_sum((double)acc, sm);
+            for (int e = 0; e < V; ++e) acc = sq_add(gf[u][e], acc);
+        const double tot = block_sum(acc, sm);
         if (threadIdx.x == 0) out[r0] = tot;
     } else {
         for (int t = r0; t < r1; ++t) {
             const int64_t lo = tiles[t].start, hi = lo + tiles[t].len;
-            float acc = 0.f;
+            double acc = 0.0;
 #pragma unroll
             for (int u = 0; u < U; ++u)
 #pragma unroll
                 for (int e = 0; e < V; ++e) {
                     const int64_t c = c0 + (int64_t)u * (GRAWA_CELL * V) + e;
-                    acc = (c >= lo && c < hi) ? fmaf(gf[u][e], gf[u][e], acc) : acc;
+                    acc = (c >= lo && c < hi) ? sq_add(gf[u][e], acc) : acc;
                 }
-            const double tot = block_sum((double)acc, sm);
+            const double tot = block_sum(acc, sm);
             if (threadIdx.x == 0) out[t] = tot;
         }
     }

@@ -8,8 +8,8 @@
 //   k_center_weights   EASGD (uniform) and LSGD (leader) weights           [App. F]
 //
 // The norm pass is a read-only stream: it runs fastest with several non-temporal loads per
-// lane in flight and a capped occupancy.  Everything after a lane's short fp32 chain is fp64,
-// summed in a fixed order (no atomics), so results are bit-reproducible.
+// lane in flight and a capped occupancy.  Squares and sums are fp64 throughout, added in a
+// fixed order (no atomics), so results are bit-reproducible.
 #include "grawa_device.h"
 
 // ---------------------------------------------------------------------------------
@@ -17,11 +17,13 @@
 // ---------------------------------------------------------------------------------
 
 // grid (n_tiles, K), block 256.  partials[k][tile] = sum over the tile of g[k][i]^2.
-// Each lane issues 8 independent 8-byte streaming loads per trip and keeps one fp32
-// accumulator per load; with the occupancy capped at 4 waves per SIMD this shape measured
-// fastest for a read-only stream on this part (7.3-7.4 TB/s; 16-byte loads at full occupancy
-// 6.9-7.0).  An accumulator chain is tile_elems/256/8 elements long (8 for the longest tile);
-// everything after the lane is fp64.
+// Each lane issues 8 independent 8-byte streaming loads per trip and keeps one accumulator
+// per load; with the occupancy capped at 4 waves per SIMD this shape measured fastest for a
+// read-only stream on this part (7.3-7.4 TB/s; 16-byte loads at full occupancy 6.9-7.0).
+// Every value is widened to fp64 before it is squared and every sum is fp64: the squares are
+// exact, so gradients of any magnitude the input type holds (1e-38 .. 3e38) give the same
+// norms as a float64 evaluation up to the order of the additions.  The pass needs under a
+// fifth of the fp64 rate at full HBM speed, so this costs no time.
 #define GRAWA_SUMSQ_U 8
 template <typename GT>
 __global__ __launch_bounds__(GRAWA_BLOCK) __attribute__((amdgpu_waves_per_eu(1, 4))) void k_sumsq(
@@ -40,18 +42,16 @@ __global__ __launch_bounds__(GRAWA_BLOCK) __attribute__((amdgpu_waves_per_eu(1, 
     int64_t b_al = b / V * V;
     if (b_al < a_al) b_al = a_al;
 
-    float acc[GRAWA_SUMSQ_U];
+    double acc[GRAWA_SUMSQ_U];
 #pragma unroll
-    for (int u = 0; u < GRAWA_SUMSQ_U; ++u) acc[u] = 0.f;
+    for (int u = 0; u < GRAWA_SUMSQ_U; ++u) acc[u] = 0.0;
 
     // unaligned head (< V elements) on the first lanes, tail on the lanes of the second wave
     if (tid < (int)(a_al - a)) {
-        const float v = Grad<GT>::one(row + a + tid);
-        acc[0] = v * v;
+        acc[0] = sq_add(Grad<GT>::one(row + a + tid), 0.0);
     }
     if (tid >= GRAWA_WAVE && tid - GRAWA_WAVE < (int)(b - b_al)) {
-        const float v = Grad<GT>::one(row + b_al + (tid - GRAWA_WAVE));
-        acc[1] = v * v;
+        acc[1] = sq_add(Grad<GT>::one(row + b_al + (tid - GRAWA_WAVE)), 0.0);
     }
 
     // Body: all loads of a trip are issued before any is used.  Full trips need no bounds
@@ -76,15 +76,15 @@ __global__ __launch_bounds__(GRAWA_BLOCK) __attribute__((amdgpu_waves_per_eu(1, 
         __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
         for (int u = 0; u < GRAWA_SUMSQ_U; ++u) {
-            const float r = Grad<GT>::sumsq8(q[u], 0.f);
-            acc[u] += (j0 + u * GRAWA_BLOCK < nvec) ? r : 0.f;
+            const double r = Grad<GT>::sumsq8(q[u], 0.0);
+            acc[u] += (j0 + u * GRAWA_BLOCK < nvec) ? r : 0.0;
         }
     }
 
     __shared__ double sm[GRAWA_BLOCK / GRAWA_WAVE];
     double lane = 0.0;
 #pragma unroll
-    for (int u = 0; u < GRAWA_SUMSQ_U; ++u) lane += (double)acc[u];
+    for (int u = 0; u < GRAWA_SUMSQ_U; ++u) lane += acc[u];
     const double total = block_sum(lane, sm);
     if (tid == 0) partials[(int64_t)k * n_tiles + blockIdx.x] = total;
 }

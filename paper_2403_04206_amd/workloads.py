@@ -121,6 +121,7 @@ class Workload:
     fused_sgd: bool = False
     log10_scale: tuple = (-3.0, 1.0)   # gradient std s = 10^U(lo, hi) per (worker, layer)
     tiny_worker: int | None = None     # this worker's gradients get std 1e-6 on every layer
+    scale_table: np.ndarray | None = None   # explicit [K, L] gradient stds (replaces the random draw)
     seed: tuple = (0, 0)
     offsets: np.ndarray = field(init=False)
 
@@ -178,6 +179,11 @@ def round_up(n, m):
 
 def grad_scales(w: Workload) -> np.ndarray:
     """s[k, l]: standard deviation of worker k's gradient in layer l."""
+    if w.scale_table is not None:
+        s = np.asarray(w.scale_table, dtype=np.float64)
+        if s.shape != (w.K, w.L):
+            raise ValueError("scale_table must be [K, L]")
+        return s
     rng = np.random.default_rng(list(w.seed) + [17])
     s = 10.0 ** rng.uniform(w.log10_scale[0], w.log10_scale[1], size=(w.K, w.L))
     if w.tiny_worker is not None:

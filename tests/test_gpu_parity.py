@@ -126,7 +126,7 @@ def test_grad_norms_table():
         assert info["n_tiles"] >= w.L
         ref = orc.layer_norms(orc.grad_sumsq(W.to_numpy_grads(g), w.offsets))
         worst = assert_table_close(A.cpu().numpy(), ref, TIGHT, "norms " + dtype)
-        assert worst < 2e-6      # fp32 chains of <= 32 squares, fp64 above: far inside the tolerance
+        assert worst < 2e-7      # squares and sums in fp64, one rounding to the float32 table
 
 
 def test_local_sgd():
