@@ -200,7 +200,12 @@ grawa_status_t grawa_local_sgd_prox(float *x, int64_t ldx, const void *g, int64_
  *   then g_mvg <- 0, t <- 0.
  * est_out (device float [K][L] or NULL) receives g_est, weights_out the weights
  * ([K][L] or [K]).  INVALID_ARG if no local step was taken since the last
- * communication.  The step counter t lives in the plan on the host: all calls on
+ * communication.  The step counter t lives in the plan's device workspace: it is
+ * advanced by the scored step's own kernels and read by the communication's, so
+ * these calls may be recorded into a HIP graph and replayed (every replay counts
+ * its steps again).  The host keeps a mirror of t as of the last enqueued call
+ * for the two INVALID_ARG checks above only; a replayed communication that finds
+ * t = 0 on the device takes all estimates as zero (plain average).  All calls on
  * one plan must come from one thread, in stream order.
  *
  * grawa_local_scores_reset: g_mvg <- 0, t <- 0 without a communication.

@@ -11,8 +11,9 @@ ROOT = os.path.dirname(PKG)
 CSRC = os.path.join(PKG, "csrc")
 LIB = os.path.join(PKG, "libgrawa.so")
 BUILD = os.path.join(PKG, "_build")
-SOURCES = [os.path.join(CSRC, n) for n in ("grawa_api.cpp", "grawa_norms.hip", "grawa_pull.hip", "grawa_local.hip")]
-HEADERS = [os.path.join(CSRC, "grawa_internal.h"), os.path.join(CSRC, "grawa_device.h"),
+SOURCES = [os.path.join(CSRC, n) for n in ("grawa_api.cpp", "grawa_maps.cpp", "grawa_norms.hip", "grawa_pull.hip",
+                                            "grawa_local.hip")]
+HEADERS = [os.path.join(CSRC, "grawa_internal.h"), os.path.join(CSRC, "grawa_device.h"), os.path.join(CSRC, "grawa_maps.h"),
            os.path.join(ROOT, "include", "grawa.h")]
 
 # Packed fp32 instructions are switched off for all device code (a hipcc flag, not a host one;
@@ -55,7 +56,7 @@ def build(force: bool = True, verbose: bool = False) -> str:
         res = subprocess.run(cmd, stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True)
         return obj, res
 
-    with ThreadPoolExecutor(max_workers=min(4, len(SOURCES))) as pool:
+    with ThreadPoolExecutor(max_workers=min(6, len(SOURCES))) as pool:
         results = list(pool.map(compile_one, SOURCES))
     objs = [o for o, _ in results]
     tmp = LIB + tag

@@ -2,71 +2,28 @@
 // and workspace) and the launch sequence of each entry point.  Nothing here computes any
 // part of the update; every step runs in the kernels of grawa_norms.hip, grawa_pull.hip and grawa_local.hip.
 #include <cmath>
-#include <cstdlib>
 #include <cstring>
 #include <new>
-#include <vector>
 
 #include "grawa_internal.h"
 
 namespace {
 
-// Norm-pass tile length: as long as possible (fewer partials, less per-block overhead) while
-// leaving at least ~8192 blocks to fill the chip; 2048 is the shortest tile that gives every lane
-// of a block one 16-byte load of bf16.
-int default_tile_elems(int K, int64_t P)
-{
-    const int64_t per_block = (int64_t)K * P / 8192;
-    int t = 16384;
-    while (t > 2048 && t > per_block) t >>= 1;
-    return t;
-}
-
-inline bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
-
 inline size_t round256(size_t n) { return (n + 255) & ~size_t(255); }
-
-int tile_elems_for(int K, int64_t P)
-{
-    // Tuning knob: GRAWA_TILE_ELEMS overrides the tile length (multiple of 8, 256 .. 1048576).
-    const int dflt = default_tile_elems(K, P);
-    const char *e = std::getenv("GRAWA_TILE_ELEMS");
-    if (!e || !*e) return dflt;
-    char *end = nullptr;
-    long v = std::strtol(e, &end, 10);
-    if (end == e || *end != '\0' || v < 256 || v > (1 << 20) || (v % 8) != 0) return dflt;
-    return (int)v;
-}
 
 grawa_status_t check_params(const grawa_plan *p, const float *x, int64_t ldx)
 {
-    if (!p || !x) return GRAWA_ERR_INVALID_ARG;
-    if (ldx < p->P) return GRAWA_ERR_INVALID_ARG;
-    if (!aligned16(x) || (ldx % 4) != 0) return GRAWA_ERR_ALIGNMENT;
-    return GRAWA_OK;
+    if (!p) return GRAWA_ERR_INVALID_ARG;
+    return grawa_check_params(p->P, x, ldx);
 }
 
-grawa_status_t check_grads(int64_t P, const void *g, int64_t ldg, grawa_dtype_t dt)
+inline grawa_status_t check_grads(int64_t P, const void *g, int64_t ldg, grawa_dtype_t dt)
 {
-    if (!g) return GRAWA_ERR_INVALID_ARG;
-    if (dt != GRAWA_F32 && dt != GRAWA_BF16) return GRAWA_ERR_UNSUPPORTED;
-    if (ldg < P) return GRAWA_ERR_INVALID_ARG;
-    const int64_t per16 = (dt == GRAWA_BF16) ? 8 : 4;
-    if (!aligned16(g) || (ldg % per16) != 0) return GRAWA_ERR_ALIGNMENT;
-    return GRAWA_OK;
+    return grawa_check_grads(P, g, ldg, dt);
 }
-
-grawa_status_t check_lambda(float lambda)
-{
-    if (!std::isfinite(lambda) || lambda < 0.f || lambda > 1.f) return GRAWA_ERR_INVALID_ARG;
-    return GRAWA_OK;
-}
-
-grawa_status_t check_center(const float *c)
-{
-    if (c && !aligned16(c)) return GRAWA_ERR_ALIGNMENT;
-    return GRAWA_OK;
-}
+inline grawa_status_t check_lambda(float lambda) { return grawa_check_lambda(lambda); }
+inline grawa_status_t check_center(const float *c) { return grawa_check_center(c); }
+inline bool aligned16(const void *p) { return grawa_aligned16(p); }
 
 struct DeviceGuard { // the plan's kernels run on the device the plan was made on
     int prev = -1;
@@ -83,8 +40,14 @@ struct DeviceGuard { // the plan's kernels run on the device the plan was made o
     }
 };
 
-// Event pair bookkeeping for the measurement aid.
+// Event bookkeeping for the measurement aid: a profiled call takes one slot of four events and
+// notes whether its norm-kernel pair was recorded.
 inline bool prof_active(const grawa_plan *p) { return p->profile_on && p->profile_n < GRAWA_PROFILE_SLOTS; }
+inline void prof_commit(grawa_plan *p, bool with_norm)
+{
+    p->ev_norm[p->profile_n] = with_norm ? 1 : 0;
+    p->profile_n += 1;
+}
 
 #define GRAWA_TRY_HIP(expr)                       \
     do {                                          \
@@ -121,7 +84,7 @@ grawa_status_t run_update(grawa_plan *p, float *x, int64_t ldx, const void *g, i
     GRAWA_TRY_HIP(grawa_launch_center_pull(p, x, ldx, per_layer ? p->d_beta_layer : p->d_beta_model,
                                            per_layer, lambda, g_sgd, ldg_sgd, dt, lr, fuse_sgd,
                                            center_out, 0.f, 0, s, prof ? ev[2] : nullptr, prof ? ev[3] : nullptr));
-    if (prof) p->profile_n += 1;
+    if (prof) prof_commit(p, true);
     return GRAWA_OK;
 }
 
@@ -165,71 +128,17 @@ static grawa_status_t plan_create_impl(grawa_plan_t **out, int K, int64_t P, int
     if (!layer_offsets_host && L != 1) return GRAWA_ERR_INVALID_ARG;
     if (K > GRAWA_MAX_WORKERS) return GRAWA_ERR_UNSUPPORTED;
 
-    std::vector<int64_t> off((size_t)L + 1);
-    if (layer_offsets_host) {
-        std::memcpy(off.data(), layer_offsets_host, sizeof(int64_t) * ((size_t)L + 1));
-    } else {
-        off[0] = 0;
-        off[1] = P;
-    }
-    if (off[0] != 0 || off[(size_t)L] != P) return GRAWA_ERR_INVALID_ARG;
-    for (int l = 0; l < L; ++l)
-        if (off[(size_t)l + 1] <= off[(size_t)l]) return GRAWA_ERR_INVALID_ARG;
+    int64_t whole[2] = {0, P};
+    const int64_t *off = layer_offsets_host ? layer_offsets_host : whole;
+    if (grawa_offsets_invalid(P, L, off)) return GRAWA_ERR_INVALID_ARG;
 
-    // Tile maps: cut every layer at the multiples of T of the flat index, so tile starts are
-    // either a multiple of T or a layer start and no tile crosses a layer boundary.  One map for
-    // the norm pass (long tiles), one for the scored local step (1024-column tiles).
-    const int T = tile_elems_for(K, P);
-    const int TR = 1024;
-    const int64_t max_tiles = (int64_t)1 << 24; // keeps grid.x * 256 below 2^32
-    if (P / T + L > max_tiles || P / TR + L > max_tiles) return GRAWA_ERR_UNSUPPORTED;
-    std::vector<GrawaTile> tiles, rtiles;
-    std::vector<int32_t> layer_tile0((size_t)L + 1), layer_rtile0((size_t)L + 1);
-    auto cut = [&](int len, std::vector<GrawaTile> &out, std::vector<int32_t> &first) {
-        out.reserve((size_t)(P / len + L + 1));
-        for (int l = 0; l < L; ++l) {
-            first[(size_t)l] = (int32_t)out.size();
-            int64_t s = off[(size_t)l];
-            const int64_t e = off[(size_t)l + 1];
-            while (s < e) {
-                int64_t stop = (s / len + 1) * len;
-                if (stop > e) stop = e;
-                out.push_back(GrawaTile{s, (int32_t)(stop - s), (int32_t)l});
-                s = stop;
-            }
-        }
-        first[(size_t)L] = (int32_t)out.size();
-    };
-    cut(T, tiles, layer_tile0);
-    cut(TR, rtiles, layer_rtile0);
-    const int64_t nt = (int64_t)tiles.size();
-    const int64_t nrt = (int64_t)rtiles.size();
-    // Short tiles never cross a multiple of TR: index them by aligned block.
-    const int64_t nrb = (P + TR - 1) / TR;
-    std::vector<int32_t> block_rtile0((size_t)nrb + 1);
-    {
-        int64_t r = 0;
-        for (int64_t m = 0; m < nrb; ++m) {
-            block_rtile0[(size_t)m] = (int32_t)r;
-            while (r < nrt && rtiles[(size_t)r].start < (m + 1) * TR) ++r;
-        }
-        block_rtile0[(size_t)nrb] = (int32_t)nrt;
-    }
-
-    // Cell map of the center+pull pass: block m covers columns [256 m, 256 m + 256).
-    const int64_t cell = 256;
-    const int64_t nc = (P + cell - 1) / cell;
-    if (nc >= max_tiles) return GRAWA_ERR_UNSUPPORTED;
-    std::vector<int32_t> cell_layer((size_t)nc);
-    {
-        int l = 0;
-        for (int64_t m = 0; m < nc; ++m) {
-            const int64_t first = m * cell;
-            const int64_t last = (first + cell < P ? first + cell : P) - 1;
-            while (off[(size_t)l + 1] <= first) ++l;
-            cell_layer[(size_t)m] = (off[(size_t)l + 1] > last) ? (int32_t)l : ~(int32_t)l;
-        }
-    }
+    const int T = grawa_default_tile_elems(K, P);
+    GrawaHostMaps m;
+    if (grawa_build_maps(P, L, off, T, m)) return GRAWA_ERR_UNSUPPORTED;
+    const int64_t nt = (int64_t)m.tiles.size();
+    const int64_t nrt = (int64_t)m.rtiles.size();
+    const int64_t nrb = (int64_t)m.block_rtile0.size() - 1;
+    const int64_t nc = (int64_t)m.cell_layer.size();
 
     grawa_plan *p = new (std::nothrow) grawa_plan();
     if (!p) return GRAWA_ERR_WORKSPACE;
@@ -258,7 +167,8 @@ static grawa_status_t plan_create_impl(grawa_plan_t **out, int K, int64_t P, int
     const size_t b_bl = b_A;
     const size_t b_bm = round256(sizeof(float) * (size_t)K);
     const size_t b_mvg = b_S;
-    p->ws_bytes = b_off + b_cells + b_tiles + b_lt0 + b_rtiles + b_lt0 + b_brt0 + b_part + b_S + b_A + b_bl + b_bm + b_mvg;
+    const size_t b_t = 256;
+    p->ws_bytes = b_off + b_cells + b_tiles + b_lt0 + b_rtiles + b_lt0 + b_brt0 + b_part + b_S + b_A + b_bl + b_bm + b_mvg + b_t;
     if (hipMalloc(&p->ws, p->ws_bytes) != hipSuccess) {
         (void)hipGetLastError();
         delete p;
@@ -277,16 +187,17 @@ static grawa_status_t plan_create_impl(grawa_plan_t **out, int K, int64_t P, int
     p->d_A = reinterpret_cast<float *>(w); w += b_A;
     p->d_beta_layer = reinterpret_cast<float *>(w); w += b_bl;
     p->d_beta_model = reinterpret_cast<float *>(w); w += b_bm;
-    p->d_mvg = reinterpret_cast<double *>(w);
+    p->d_mvg = reinterpret_cast<double *>(w); w += b_mvg;
+    p->d_local_t = reinterpret_cast<int64_t *>(w);
 
-    if (hipMemcpy(p->d_off, off.data(), sizeof(int64_t) * ((size_t)L + 1), hipMemcpyHostToDevice) != hipSuccess ||
-        hipMemcpy(p->d_cell_layer, cell_layer.data(), sizeof(int32_t) * (size_t)nc, hipMemcpyHostToDevice) != hipSuccess ||
-        hipMemcpy(p->d_tiles, tiles.data(), sizeof(GrawaTile) * (size_t)nt, hipMemcpyHostToDevice) != hipSuccess ||
-        hipMemcpy(p->d_layer_tile0, layer_tile0.data(), sizeof(int32_t) * ((size_t)L + 1), hipMemcpyHostToDevice) != hipSuccess ||
-        hipMemcpy(p->d_rtiles, rtiles.data(), sizeof(GrawaTile) * (size_t)nrt, hipMemcpyHostToDevice) != hipSuccess ||
-        hipMemcpy(p->d_layer_rtile0, layer_rtile0.data(), sizeof(int32_t) * ((size_t)L + 1), hipMemcpyHostToDevice) != hipSuccess ||
-        hipMemcpy(p->d_block_rtile0, block_rtile0.data(), sizeof(int32_t) * ((size_t)nrb + 1), hipMemcpyHostToDevice) != hipSuccess ||
-        hipMemset(p->d_partials, 0, b_part + b_S + b_A + b_bl + b_bm + b_mvg) != hipSuccess) {
+    if (hipMemcpy(p->d_off, off, sizeof(int64_t) * ((size_t)L + 1), hipMemcpyHostToDevice) != hipSuccess ||
+        hipMemcpy(p->d_cell_layer, m.cell_layer.data(), sizeof(int32_t) * (size_t)nc, hipMemcpyHostToDevice) != hipSuccess ||
+        hipMemcpy(p->d_tiles, m.tiles.data(), sizeof(GrawaTile) * (size_t)nt, hipMemcpyHostToDevice) != hipSuccess ||
+        hipMemcpy(p->d_layer_tile0, m.layer_tile0.data(), sizeof(int32_t) * ((size_t)L + 1), hipMemcpyHostToDevice) != hipSuccess ||
+        hipMemcpy(p->d_rtiles, m.rtiles.data(), sizeof(GrawaTile) * (size_t)nrt, hipMemcpyHostToDevice) != hipSuccess ||
+        hipMemcpy(p->d_layer_rtile0, m.layer_rtile0.data(), sizeof(int32_t) * ((size_t)L + 1), hipMemcpyHostToDevice) != hipSuccess ||
+        hipMemcpy(p->d_block_rtile0, m.block_rtile0.data(), sizeof(int32_t) * ((size_t)nrb + 1), hipMemcpyHostToDevice) != hipSuccess ||
+        hipMemset(p->d_partials, 0, b_part + b_S + b_A + b_bl + b_bm + b_mvg + b_t) != hipSuccess) {
         (void)hipFree(p->ws);
         delete p;
         return GRAWA_ERR_HIP;
@@ -303,6 +214,7 @@ grawa_status_t grawa_plan_destroy(grawa_plan_t *p)
         for (int i = 0; i < 4 * GRAWA_PROFILE_SLOTS; ++i)
             if (p->ev[i]) (void)hipEventDestroy(p->ev[i]);
         delete[] p->ev;
+        delete[] p->ev_norm;
     }
     if (p->ws && hipFree(p->ws) != hipSuccess) st = GRAWA_ERR_HIP;
     delete p;
@@ -380,10 +292,7 @@ grawa_status_t grawa_center_pull(grawa_plan_t *p, float *x, int64_t ldx, const f
     GRAWA_TRY_HIP(grawa_launch_center_pull(p, x, ldx, weights, per_layer ? 1 : 0, lambda, nullptr, 0, GRAWA_F32,
                                            0.f, 0, center_out, 0.f, 0, s, prof ? ev[2] : nullptr,
                                            prof ? ev[3] : nullptr));
-    if (prof) {
-        p->profile_pull_only = 1;
-        p->profile_n += 1;
-    }
+    if (prof) prof_commit(p, false);
     return GRAWA_OK;
 }
 
@@ -503,17 +412,13 @@ grawa_status_t local_update(grawa_plan_t *p, float *x, int64_t ldx, int per_laye
     if (p->local_t < 1) return GRAWA_ERR_INVALID_ARG; /* no local step since the last communication */
     DeviceGuard guard(p->device);
     if (!guard.ok) return GRAWA_ERR_HIP;
-    const double scale = p->local_gamma / (1.0 - std::pow(p->local_gamma, (double)p->local_t));
-    GRAWA_TRY_HIP(grawa_launch_local_weights(p, scale, per_layer, weights_out, est_out, s));
+    GRAWA_TRY_HIP(grawa_launch_local_weights(p, p->local_gamma, per_layer, weights_out, est_out, s));
     const bool prof = prof_active(p);
     hipEvent_t *ev = prof ? p->ev + 4 * (size_t)p->profile_n : nullptr;
     GRAWA_TRY_HIP(grawa_launch_center_pull(p, x, ldx, per_layer ? p->d_beta_layer : p->d_beta_model, per_layer,
                                            lambda, nullptr, 0, GRAWA_F32, 0.f, 0, center_out, 0.f, 0, s,
                                            prof ? ev[2] : nullptr, prof ? ev[3] : nullptr));
-    if (prof) {
-        p->profile_pull_only = 1;
-        p->profile_n += 1;
-    }
+    if (prof) prof_commit(p, false);
     GRAWA_TRY_HIP(grawa_launch_zero_estimate(p, s));
     p->local_t = 0;
     return GRAWA_OK;
@@ -549,14 +454,25 @@ grawa_status_t grawa_plan_profile(grawa_plan_t *p, int enable)
     DeviceGuard guard(p->device);
     if (!guard.ok) return GRAWA_ERR_HIP;
     if (enable && !p->ev) {
-        p->ev = new (std::nothrow) hipEvent_t[4 * GRAWA_PROFILE_SLOTS]();
-        if (!p->ev) return GRAWA_ERR_WORKSPACE;
-        for (int i = 0; i < 4 * GRAWA_PROFILE_SLOTS; ++i)
-            if (hipEventCreate(&p->ev[i]) != hipSuccess) return GRAWA_ERR_HIP;
+        const int n = 4 * GRAWA_PROFILE_SLOTS;
+        hipEvent_t *ev = new (std::nothrow) hipEvent_t[n]();
+        unsigned char *flags = new (std::nothrow) unsigned char[GRAWA_PROFILE_SLOTS]();
+        bool ok = ev && flags;
+        for (int i = 0; ok && i < n; ++i) ok = hipEventCreate(&ev[i]) == hipSuccess;
+        if (!ok) { // give back whatever was created
+            const bool no_mem = !ev || !flags;
+            if (ev)
+                for (int i = 0; i < n; ++i)
+                    if (ev[i]) (void)hipEventDestroy(ev[i]);
+            delete[] ev;
+            delete[] flags;
+            return no_mem ? GRAWA_ERR_WORKSPACE : GRAWA_ERR_HIP;
+        }
+        p->ev = ev;
+        p->ev_norm = flags;
     }
     p->profile_on = enable ? 1 : 0;
     p->profile_n = 0;
-    p->profile_pull_only = 0;
     return GRAWA_OK;
 }
 
@@ -566,7 +482,7 @@ grawa_status_t grawa_plan_profile_read(grawa_plan_t *p, int *n_calls, double *no
     double a = 0.0, b = 0.0;
     for (int i = 0; i < p->profile_n; ++i) {
         float ms = 0.f;
-        if (!p->profile_pull_only) {
+        if (p->ev_norm[i]) {
             GRAWA_TRY_HIP(hipEventElapsedTime(&ms, p->ev[4 * i + 0], p->ev[4 * i + 1]));
             a += ms;
         }
@@ -585,7 +501,7 @@ grawa_status_t grawa_plan_profile_read_call(grawa_plan_t *p, int i, double *norm
     float a = 0.f, b = 0.f, c = 0.f;
     GRAWA_TRY_HIP(hipEventElapsedTime(&b, p->ev[4 * i + 2], p->ev[4 * i + 3]));
     c = b;
-    if (!p->profile_pull_only) {
+    if (p->ev_norm[i]) {
         GRAWA_TRY_HIP(hipEventElapsedTime(&a, p->ev[4 * i + 0], p->ev[4 * i + 1]));
         GRAWA_TRY_HIP(hipEventElapsedTime(&c, p->ev[4 * i + 0], p->ev[4 * i + 3]));
     }

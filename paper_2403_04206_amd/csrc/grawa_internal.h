@@ -6,15 +6,10 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
-#include "grawa.h"
+#include <cmath>
 
-// One tile of the flat vector for the norm pass.  A tile never crosses a layer boundary, so
-// its sum of squares belongs to one layer.  16 bytes: fetched with one scalar load.
-struct GrawaTile {
-    int64_t start; // first element (index into a row)
-    int32_t len;   // 1 .. tile_elems
-    int32_t layer; // layer the tile lies in
-};
+#include "grawa.h"
+#include "grawa_maps.h"
 
 #define GRAWA_PROFILE_SLOTS 4096
 
@@ -43,14 +38,47 @@ struct grawa_plan {
     float *d_beta_layer;    // [K][L] per-layer weights
     float *d_beta_model;    // [K] model-level weights
     double *d_mvg;          // [K][L] moving average of the layer norms (running estimate, Appendix G)
-    int64_t local_t;        // local steps since the last communication
+    int64_t *d_local_t;     // device: local steps since the last communication (what the kernels use)
+    int64_t local_t;        // host mirror of the counter as of the last enqueued call (argument checks only)
     double local_gamma;     // momentum of the running estimate used so far (0 = none yet)
     // measurement aid
     int profile_on;
     int profile_n;
-    int profile_pull_only; // set when grawa_center_pull was profiled (no norm-kernel events)
-    hipEvent_t *ev; // 4 per slot: norm begin/end, pull begin/end
+    hipEvent_t *ev;          // 4 per slot: norm begin/end, pull begin/end
+    unsigned char *ev_norm;  // per slot: 1 if the call recorded norm-kernel events
 };
+
+// Argument checks shared by the entry points (host only; nothing is launched on failure).
+static inline bool grawa_aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+
+static inline grawa_status_t grawa_check_params(int64_t P, const float *x, int64_t ldx)
+{
+    if (!x || ldx < P) return GRAWA_ERR_INVALID_ARG;
+    if (!grawa_aligned16(x) || (ldx % 4) != 0) return GRAWA_ERR_ALIGNMENT;
+    return GRAWA_OK;
+}
+
+static inline grawa_status_t grawa_check_grads(int64_t P, const void *g, int64_t ldg, grawa_dtype_t dt)
+{
+    if (!g) return GRAWA_ERR_INVALID_ARG;
+    if (dt != GRAWA_F32 && dt != GRAWA_BF16) return GRAWA_ERR_UNSUPPORTED;
+    if (ldg < P) return GRAWA_ERR_INVALID_ARG;
+    const int64_t per16 = (dt == GRAWA_BF16) ? 8 : 4;
+    if (!grawa_aligned16(g) || (ldg % per16) != 0) return GRAWA_ERR_ALIGNMENT;
+    return GRAWA_OK;
+}
+
+static inline grawa_status_t grawa_check_lambda(float lambda)
+{
+    if (!std::isfinite(lambda) || lambda < 0.f || lambda > 1.f) return GRAWA_ERR_INVALID_ARG;
+    return GRAWA_OK;
+}
+
+static inline grawa_status_t grawa_check_center(const float *c)
+{
+    if (c && !grawa_aligned16(c)) return GRAWA_ERR_ALIGNMENT;
+    return GRAWA_OK;
+}
 
 // Launchers (defined next to their kernels).  All return the hipError_t of the launch.
 // e0/e1: optional start/stop events of the launch itself (null when not profiling).
@@ -58,7 +86,7 @@ hipError_t grawa_launch_sumsq(const grawa_plan *p, const void *g, int64_t ldg, g
                               hipStream_t s, hipEvent_t e0, hipEvent_t e1);
 hipError_t grawa_launch_finalize_layers(const grawa_plan *p, float *norms_user, float *beta_user,
                                         hipStream_t s, int update_estimate, double gamma);
-hipError_t grawa_launch_local_weights(const grawa_plan *p, double scale, int per_layer, float *beta_user,
+hipError_t grawa_launch_local_weights(const grawa_plan *p, double gamma, int per_layer, float *beta_user,
                                       float *est_user, hipStream_t s);
 hipError_t grawa_launch_zero_estimate(const grawa_plan *p, hipStream_t s);
 hipError_t grawa_launch_row_step(float *x, int64_t ldx, const void *g, int64_t ldg, grawa_dtype_t dt, float lr,

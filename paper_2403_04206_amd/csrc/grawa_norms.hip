@@ -152,11 +152,15 @@ __device__ __forceinline__ double wave_strided_sum(const double *__restrict__ p,
 __global__ __launch_bounds__(GRAWA_FIN_BLOCK) void k_finalize_layers(
     const double *__restrict__ partials, int64_t n_tiles, const int32_t *__restrict__ layer_tile0,
     int K, int L, double *__restrict__ S, float *__restrict__ A, float *__restrict__ A_user,
-    float *__restrict__ beta, float *__restrict__ beta_user, double *__restrict__ mvg, double gamma)
+    float *__restrict__ beta, float *__restrict__ beta_user, double *__restrict__ mvg, double gamma,
+    int64_t *__restrict__ local_t)
 {
     __shared__ double sA[GRAWA_MAX_WORKERS];
     __shared__ double sw[GRAWA_FIN_WAVES];
     const int l = blockIdx.x;
+    // One more local step has fed the running estimate (Appendix G: t <- t + 1).  The counter lives
+    // on the device so that a recorded and replayed call still counts.
+    if (mvg && l == 0 && threadIdx.x == 0) *local_t += 1;
     const int t0 = layer_tile0[l], t1 = layer_tile0[l + 1];
     const int lane = threadIdx.x & (GRAWA_WAVE - 1);
     const int wave = threadIdx.x / GRAWA_WAVE;
@@ -197,11 +201,14 @@ __global__ __launch_bounds__(GRAWA_FIN_BLOCK) void k_finalize_layers(
     if (wave == 0) group_weights(sA, K, beta + l, L, beta_user ? beta_user + l : nullptr);
 }
 
-// Weights from the running norm estimate g_est = scale * g_mvg (Appendix G; scale =
-// gamma / (1 - gamma^t)).  per_layer: grid L, block l normalises column l over the workers
-// (eq. (7)); otherwise grid 1: score of worker k is the sum of its layer estimates (eq. (3)
-// applied to the estimates), then eq. (4).  est_user (float [K][L], may be null) receives g_est.
-__global__ __launch_bounds__(GRAWA_FIN_BLOCK) void k_local_weights(const double *__restrict__ mvg, double scale,
+// Weights from the running norm estimate g_est = gamma g_mvg / (1 - gamma^t) (Appendix G), t =
+// the device-side count of local steps since the last communication.  per_layer: grid L, block
+// l normalises column l over the workers (eq. (7)); otherwise grid 1: score of worker k is the
+// sum of its layer estimates (eq. (3) applied to the estimates), then eq. (4).  est_user (float
+// [K][L], may be null) receives g_est.  With t = 0 (no step was counted) the estimates are taken
+// as zero, which the zero-norm rule turns into the plain average.
+__global__ __launch_bounds__(GRAWA_FIN_BLOCK) void k_local_weights(const double *__restrict__ mvg, double gamma,
+                                                                   const int64_t *__restrict__ local_t,
                                                                    int K, int L, int per_layer,
                                                                    float *__restrict__ beta,
                                                                    float *__restrict__ beta_user,
@@ -210,6 +217,8 @@ __global__ __launch_bounds__(GRAWA_FIN_BLOCK) void k_local_weights(const double 
     __shared__ double sA[GRAWA_MAX_WORKERS];
     const int lane = threadIdx.x & (GRAWA_WAVE - 1);
     const int wave = threadIdx.x / GRAWA_WAVE;
+    const int64_t t = *local_t;
+    const double scale = t > 0 ? gamma / (1.0 - pow(gamma, (double)t)) : 0.0;
     if (per_layer) {
         const int l = blockIdx.x;
         for (int k = threadIdx.x; k < K; k += GRAWA_FIN_BLOCK) {
@@ -235,10 +244,13 @@ __global__ __launch_bounds__(GRAWA_FIN_BLOCK) void k_local_weights(const double 
     }
 }
 
-__global__ __launch_bounds__(GRAWA_BLOCK) void k_zero_f64(double *__restrict__ p, int64_t n)
+// g_mvg <- 0 and t <- 0 (after a communication, or an explicit reset).
+__global__ __launch_bounds__(GRAWA_BLOCK) void k_zero_estimate(double *__restrict__ p, int64_t n,
+                                                               int64_t *__restrict__ local_t)
 {
     const int64_t i = (int64_t)blockIdx.x * GRAWA_BLOCK + threadIdx.x;
     if (i < n) p[i] = 0.0;
+    if (i == 0) *local_t = 0;
 }
 
 // grid 1, block 1024.  Model-level score per worker from the [K][L] squared layer norms:
@@ -315,23 +327,24 @@ hipError_t grawa_launch_finalize_layers(const grawa_plan *p, float *norms_user, 
     k_finalize_layers<<<dim3((unsigned)p->L), dim3(GRAWA_FIN_BLOCK), 0, s>>>(
         p->d_partials, update_estimate ? p->n_rtiles : p->n_tiles,
         update_estimate ? p->d_layer_rtile0 : p->d_layer_tile0, p->K, p->L, p->d_S, p->d_A, norms_user,
-        p->d_beta_layer, beta_user, update_estimate ? p->d_mvg : nullptr, gamma);
+        p->d_beta_layer, beta_user, update_estimate ? p->d_mvg : nullptr, gamma, p->d_local_t);
     return hipGetLastError();
 }
 
-hipError_t grawa_launch_local_weights(const grawa_plan *p, double scale, int per_layer, float *beta_user,
+hipError_t grawa_launch_local_weights(const grawa_plan *p, double gamma, int per_layer, float *beta_user,
                                       float *est_user, hipStream_t s)
 {
     k_local_weights<<<dim3(per_layer ? (unsigned)p->L : 1u), dim3(GRAWA_FIN_BLOCK), 0, s>>>(
-        p->d_mvg, scale, p->K, p->L, per_layer, per_layer ? p->d_beta_layer : p->d_beta_model, beta_user,
-        est_user);
+        p->d_mvg, gamma, p->d_local_t, p->K, p->L, per_layer, per_layer ? p->d_beta_layer : p->d_beta_model,
+        beta_user, est_user);
     return hipGetLastError();
 }
 
 hipError_t grawa_launch_zero_estimate(const grawa_plan *p, hipStream_t s)
 {
     const int64_t n = (int64_t)p->K * p->L;
-    k_zero_f64<<<dim3((unsigned)((n + GRAWA_BLOCK - 1) / GRAWA_BLOCK)), dim3(GRAWA_BLOCK), 0, s>>>(p->d_mvg, n);
+    k_zero_estimate<<<dim3((unsigned)((n + GRAWA_BLOCK - 1) / GRAWA_BLOCK)), dim3(GRAWA_BLOCK), 0, s>>>(p->d_mvg, n,
+                                                                                                    p->d_local_t);
     return hipGetLastError();
 }
 

@@ -141,3 +141,69 @@ def test_two_rounds_and_reset():
     r2 = orc.local_grawa_round(np.ascontiguousarray(x2), [gh, gh2], w.offsets, 0.1, 0.4, 0.7, "mgrawa")
     sc = scale_of(xh, P, [gh, gh2, gh, gh2], 0.1)
     assert_params_close(xg.cpu().numpy()[:, :P], r2["x"], w.offsets, 3 * TIGHT, "two rounds", sc)
+
+
+def test_local_round_replayed_from_a_captured_graph():
+    # The step counter t of Appendix G lives on the device, so a recorded round -- two scored local
+    # steps and the communication -- counts its steps again on every replay: each replay must give bit
+    # for bit what the same calls give eagerly.  A second graph holds one scored step only; replaying
+    # it three times and then communicating eagerly must equal three eager steps and a communication.
+    K = 8
+    w, x, g1 = W.make_small(701, K, RAGGED, device=DEV)
+    _, _, g2 = W.make_small(702, K, RAGGED, device=DEV)
+    P, L = w.P, w.L
+    say("local round under graph capture K=%d P=%d" % (K, P))
+    lr, lam, gamma = 0.05, 0.3, 0.9
+    xs = x.clone()
+    est_e, est_g = torch.empty((K, L), device=DEV), torch.empty((K, L), device=DEV)
+    wts_e, wts_g = torch.empty((K, L), device=DEV), torch.empty((K, L), device=DEV)
+    cen_e, cen_g = torch.empty(W.round_up(P, 4), device=DEV), torch.empty(W.round_up(P, 4), device=DEV)
+
+    def round_(plan, xt, est, wts, cen):
+        plan.local_step_scored(xt[:, :P], g1[:, :P], lr, gamma)
+        plan.local_step_scored(xt[:, :P], g2[:, :P], lr, gamma)
+        plan.local_lgrawa_update(xt[:, :P], lam, center_out=cen, weights_out=wts, est_out=est)
+
+    with grawa.Plan(K, P, w.offsets) as eager, grawa.Plan(K, P, w.offsets) as rec:
+        side = torch.cuda.Stream()
+        side.wait_stream(torch.cuda.current_stream())
+        with torch.cuda.stream(side):                      # warm-up outside the capture
+            round_(rec, xs, est_g, wts_g, cen_g)
+        torch.cuda.current_stream().wait_stream(side)
+        torch.cuda.synchronize()
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph):
+            round_(rec, xs, est_g, wts_g, cen_g)
+        for rep in range(3):
+            xe = x.clone() + rep                            # eager work between the replays
+            xs.copy_(xe)
+            round_(eager, xe, est_e, wts_e, cen_e)
+            graph.replay()
+            torch.cuda.synchronize()
+            assert torch.equal(xs, xe), "replay %d differs from the eager calls" % rep
+            assert torch.equal(est_g, est_e) and torch.equal(wts_g, wts_e) and torch.equal(cen_g[:P], cen_e[:P])
+        # one recorded step, replayed three times, then an eager communication on the same plan
+        step_graph = torch.cuda.CUDAGraph()
+        xs.copy_(x)
+        torch.cuda.synchronize()
+        with torch.cuda.graph(step_graph):
+            rec.local_step_scored(xs[:, :P], g1[:, :P], lr, gamma)
+        xs.copy_(x)
+        rec.local_scores_reset()
+        for _ in range(3):
+            step_graph.replay()
+        rec.local_step_scored(xs[:, :P], g2[:, :P], lr, gamma)     # keeps the host-side check satisfied too
+        rec.local_lgrawa_update(xs[:, :P], lam, est_out=est_g, weights_out=wts_g)
+        xe = x.clone()
+        for _ in range(3):
+            eager.local_step_scored(xe[:, :P], g1[:, :P], lr, gamma)
+        eager.local_step_scored(xe[:, :P], g2[:, :P], lr, gamma)
+        eager.local_lgrawa_update(xe[:, :P], lam, est_out=est_e, weights_out=wts_e)
+        torch.cuda.synchronize()
+        assert torch.equal(est_g, est_e) and torch.equal(wts_g, wts_e) and torch.equal(xs, xe)
+    # and the eager result is the reference's (t = 4 steps)
+    ghs = [W.to_numpy_grads(g1)] * 3 + [W.to_numpy_grads(g2)]
+    ref = orc.local_grawa_round(W.to_numpy_params(x), ghs, w.offsets, lr, lam, gamma, "lgrawa")
+    assert_table_close(est_e.cpu().numpy(), ref["g_est"], TIGHT, "g_est after 4 steps")
+    assert_params_close(xe.cpu().numpy()[:, :P], ref["x"], w.offsets, TIGHT, "x after 4 steps",
+                        scale_of(W.to_numpy_params(x), P, ghs, lr))
