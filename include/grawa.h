@@ -258,6 +258,37 @@ grawa_status_t grawa_lsgd_update(grawa_plan_t *plan, float *x, int64_t ldx, cons
                                  float lambda, float *center_out, int *leader_out, void *stream);
 
 /*
+ * grawa_lgrawa_update without any allocation, for callers that cannot call
+ * hipMalloc: code under HIP graph capture, tight serving loops, harnesses that
+ * forbid allocation.  It needs no plan.  The workspace a plan would own (tile
+ * map, cell map, per-tile partial sums, the K x L tables) lives in a fixed
+ * 32 MiB array inside the library's device image, one copy per GPU, held until
+ * the process ends; the maps are built by two small kernels from layer offsets
+ * that are already in DEVICE memory.  The call enqueues kernels on `stream` and
+ * nothing else (no hipMalloc / hipFree / memset / copy, no synchronisation), and
+ * gives bit for bit what grawa_lgrawa_update gives for the same inputs.
+ *   layer_offsets_dev   device int64 [L+1], 8-byte aligned: [0] = 0, strictly
+ *                       increasing, [L] = P.  They cannot be checked from the
+ *                       host: offsets that break the rule give meaningless
+ *                       values, but every access stays inside the buffers.
+ *   x, g, lambda, center_out, weights_out: as in grawa_lgrawa_update.
+ * Limits: K <= GRAWA_MAX_WORKERS, and the workspace must fit the array:
+ *   4*ceil(P/256) + (16 + 8K)*(P/T + L + 1) + 16*K*L + 4K + 4L bytes (each part
+ *   rounded up to 256) <= 32 MiB, T the tile length a plan would pick (2048 ..
+ *   16384); the largest benchmark configuration (P = 354 M, K = 8) needs 7 MiB.
+ *   Beyond that:
+ *   GRAWA_ERR_UNSUPPORTED, nothing launched.
+ * All calls on one GPU share that GPU's array: calls that may overlap on one GPU
+ * (two streams, two threads) race and must be ordered by the caller.  The
+ * first call on a device looks up the array's address (no allocation, but do
+ * not make it while a capture is in progress on that device).
+ */
+grawa_status_t grawa_lgrawa_update_static(int K, int64_t P, int L, const int64_t *layer_offsets_dev,
+                                          float *x, int64_t ldx, const void *g, int64_t ldg,
+                                          grawa_dtype_t g_dtype, float lambda, float *center_out,
+                                          float *weights_out, void *stream);
+
+/*
  * Measurement aids (not part of the method).
  *
  * grawa_plan_profile: with enable != 0 the plan attaches a start and a stop

@@ -12,7 +12,7 @@ CSRC = os.path.join(PKG, "csrc")
 LIB = os.path.join(PKG, "libgrawa.so")
 BUILD = os.path.join(PKG, "_build")
 SOURCES = [os.path.join(CSRC, n) for n in ("grawa_api.cpp", "grawa_maps.cpp", "grawa_norms.hip", "grawa_pull.hip",
-                                            "grawa_local.hip")]
+                                            "grawa_local.hip", "grawa_static.hip")]
 HEADERS = [os.path.join(CSRC, "grawa_internal.h"), os.path.join(CSRC, "grawa_device.h"), os.path.join(CSRC, "grawa_maps.h"),
            os.path.join(ROOT, "include", "grawa.h")]
 

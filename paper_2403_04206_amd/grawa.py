@@ -64,6 +64,7 @@ def lib():
         "grawa_local_nesterov": (it, [vp, i64, vp, i64, it, vp, i64, it, i64, fl, fl, fl, vp]),
         "grawa_easgd_update": (it, [vp, vp, i64, fl, fl, vp, vp]),
         "grawa_lsgd_update": (it, [vp, vp, i64, vp, fl, vp, vp, vp]),
+        "grawa_lgrawa_update_static": (it, [it, i64, it, vp, vp, i64, vp, i64, it, fl, vp, vp, vp]),
         "grawa_plan_profile": (it, [vp, it]),
         "grawa_plan_profile_read": (it, [vp, C.POINTER(it), C.POINTER(dbl), C.POINTER(dbl)]),
         "grawa_plan_profile_read_call": (it, [vp, it, C.POINTER(dbl), C.POINTER(dbl), C.POINTER(dbl)]),
@@ -281,6 +282,21 @@ def local_nesterov(x, g, buf, lr, momentum, weight_decay=0.0, P=None, stream=Non
     P = x.shape[1] if P is None else int(P)
     _check(lib().grawa_local_nesterov(xp, ldx, gp, ldg, dt, bp, ldb, K, P, float(lr), float(momentum),
                                       float(weight_decay), _stream(stream)), "grawa_local_nesterov")
+
+
+def lgrawa_update_static(x, g, layer_offsets_dev, lam, center_out=None, weights_out=None, P=None, stream=None):
+    """grawa_lgrawa_update_static: the LGRAWA update without a plan and without any allocation;
+    layer_offsets_dev is an int64 CUDA tensor [L+1]."""
+    xp, ldx = _params(x)
+    gp, ldg, dt = _grads(g)
+    off = layer_offsets_dev
+    if off.dtype != torch.int64 or off.dim() != 1 or not off.is_cuda or not off.is_contiguous() or off.numel() < 2:
+        raise TypeError("layer_offsets_dev must be a contiguous int64 CUDA tensor [L+1]")
+    K = x.shape[0]
+    P = x.shape[1] if P is None else int(P)
+    _check(lib().grawa_lgrawa_update_static(K, P, off.numel() - 1, _ptr(off), xp, ldx, gp, ldg, dt, float(lam),
+                                            _ptr(center_out), _ptr(weights_out), _stream(stream)),
+           "grawa_lgrawa_update_static")
 
 
 def stream_copy(dst, src, stream=None):
