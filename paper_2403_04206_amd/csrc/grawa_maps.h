@@ -4,6 +4,7 @@
 #ifndef GRAWA_MAPS_H
 #define GRAWA_MAPS_H
 
+#include <stddef.h>
 #include <stdint.h>
 
 #include <vector>

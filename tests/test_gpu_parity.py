@@ -258,10 +258,12 @@ def test_errors_launch_nothing():
         with pytest.raises(grawa.GrawaError) as e:                      # row stride not a multiple of 16 bytes
             plan.lgrawa_update(torch.zeros((4, ld + 2), device=DEV)[:, :P], g[:, :P], 0.1)
         assert e.value.status == grawa.ERR_ALIGNMENT
-        short = torch.empty((4, W.round_up(P, 8) - 8), device=DEV)       # ld < P
-        with pytest.raises(grawa.GrawaError) as e:
+        short = torch.empty((4, W.round_up(P, 8) - 8), device=DEV)       # fewer than P columns: the binding refuses
+        with pytest.raises(ValueError):
             plan.lgrawa_update(short, g[:, :P], 0.1)
-        assert e.value.status == grawa.ERR_INVALID_ARG
+        st = grawa.lib().grawa_lgrawa_update(plan._h, short.data_ptr(), short.stride(0), g.data_ptr(), g.stride(0), 0,
+                                             0.1, None, None, None)    # and so does the library itself (ld < P)
+        assert st == grawa.ERR_INVALID_ARG
         with pytest.raises(grawa.GrawaError) as e:
             plan.lgrawa_update_sgd(x[:, :P], g[:, :P], 0.1, g[:, :P], float("nan"))
         assert e.value.status == grawa.ERR_INVALID_ARG
