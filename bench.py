@@ -13,10 +13,14 @@ fused) divided by the measured time per step.  `roofline` is the same kind of fi
 dominant kernel alone (center+pull), from HIP start/stop events attached to that kernel's
 launches while the timed steps are repeated once more (so that `value` carries no event
 overhead).  `cpu_baseline` is the float64 CPU reference timed on a bounded sample of the
-same workload on this machine's host cores.  `phases` times the calls around the distributed
-phase (local steps, Local-GRAWA round, Nesterov step, EASGD / LSGD) on the same workload.
+same workload on this machine's host cores.  The headline workload is the largest of the five
+configurations (configuration 3); `roofline_by_config` and `cpu_baseline_by_config` carry the same
+two objects for each of the three configurations the throughput target is stated for (2, 3, 4),
+`all_configs` the timing of all five.  `phases` times the calls around the distributed phase
+(local steps, Local-GRAWA round, Nesterov step, EASGD / LSGD) on the headline workload.
 """
 import argparse
+import hashlib
 import json
 import os
 import sys
@@ -27,6 +31,9 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBPS = 8000.0
+HEADLINE_CONFIG = 3            # the largest single-GPU configuration (354 M parameters x 8 workers, 28 GB per update)
+TARGET_CONFIGS = (2, 3, 4)     # the configurations the throughput target is stated for
+TRAFFIC_FILE = os.path.join("profiles", "traffic.json")
 
 
 def parse():
@@ -34,11 +41,13 @@ def parse():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=3)
-    ap.add_argument("--config", type=int, default=2, help="benchmark configuration 0..4 (headline: 2)")
+    ap.add_argument("--config", type=int, default=HEADLINE_CONFIG,
+                    help="benchmark configuration 0..4 of the headline figures (default: %d)" % HEADLINE_CONFIG)
     ap.add_argument("--variant", default=None, help="lgrawa | mgrawa (default: the configuration's)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-sweep", action="store_true", help="do not also time the other configurations")
-    ap.add_argument("--cpu-seconds", type=float, default=15.0, help="target CPU time of the reference sample")
+    ap.add_argument("--cpu-seconds", type=float, default=10.0,
+                    help="target CPU time of the reference sample, per configuration")
     ap.add_argument("--no-phases", action="store_true", help="do not also time the local-phase and Appendix F calls")
     ap.add_argument("--only-phases", action="store_true",
                     help="time only the local-phase and Appendix F calls on --config (for kernel profiles)")
@@ -304,24 +313,61 @@ def cpu_baseline(torch, W, w, variant, target_seconds):
     }
 
 
+def kernel_source_hash():
+    """Hash of the library's kernel and host sources: counter figures taken from an older build are not
+    reported for a newer one."""
+    src = os.path.join(ROOT, "paper_2403_04206_amd", "csrc")
+    h = hashlib.sha256()
+    for name in sorted(os.listdir(src)):
+        with open(os.path.join(src, name), "rb") as f:
+            h.update(f.read())
+    return h.hexdigest()[:16]
+
+
 def measured_traffic(workload, variant):
-    """HBM bytes per launch of the center+pull kernel from the committed rocprofv3 counter runs
-    (profiles/traffic.txt), or None when there is no entry for this workload or the library
-    sources have changed since the counters were taken."""
-    from paper_2403_04206_amd import profile_summary
-    path = os.path.join(ROOT, "profiles", "traffic.txt")
+    """(bytes, source): HBM bytes per launch of the center+pull kernel from the committed rocprofv3
+    counter runs (profiles/traffic.json: FETCH_SIZE and WRITE_SIZE, each scaled by what it reads for the
+    plain copy kernel in the same run).  bytes is None when there is no entry for this workload or the
+    library sources have changed since the counters were taken."""
     try:
-        with open(path) as f:
+        with open(os.path.join(ROOT, TRAFFIC_FILE)) as f:
             tj = json.load(f)
     except (OSError, ValueError):
-        return None
-    if tj.get("source_hash") != profile_summary.kernel_source_hash():
-        return None
+        return None, "no %s" % TRAFFIC_FILE
+    have, now = tj.get("source_hash"), kernel_source_hash()
+    if have != now:
+        return None, "%s was taken from library sources %s, this build is %s" % (TRAFFIC_FILE, have, now)
     entry = tj.get("workloads", {}).get(workload)
     if not entry or entry.get("variant") != variant:
-        return None
+        return None, "%s has no entry for %s (%s)" % (TRAFFIC_FILE, workload, variant)
     k = entry.get("kernels", {}).get("k_center_pull")
-    return k["total_bytes"] if k else None
+    if not k:
+        return None, "%s has no center+pull entry for %s" % (TRAFFIC_FILE, workload)
+    return k["total_bytes"], ("%s: rocprofv3 --pmc FETCH_SIZE and --pmc WRITE_SIZE runs of this file, scaled by the "
+                              "copy kernel of the same run (x%.3f, x%.3f); library sources %s; not re-measured in this "
+                              "run" % (TRAFFIC_FILE, entry["fetch_scale"], entry["write_scale"], have))
+
+
+def roofline_of(stats):
+    """The roofline object of one timed configuration: the center+pull kernel (dominant), with the norm kernel
+    beside it."""
+    traffic, source = measured_traffic(stats["workload"], stats["variant"])
+    return {
+        "bound": "hbm", "kernel": "k_center_pull", "achieved": stats["pull_kernel_GBps"], "peak": HBM_PEAK_GBPS,
+        "unit": "GB/s", "frac": (stats["pull_kernel_GBps"] or 0.0) / HBM_PEAK_GBPS,
+        "traffic": traffic, "traffic_source": source,
+        "bytes_per_launch": stats["pull_kernel_bytes"], "avg_launch_ms": stats["pull_kernel_ms"],
+        "launch_ms": stats["pull_kernel_ms_spread"],
+        "norm_kernel": {"kernel": "k_sumsq", "achieved": stats["norm_kernel_GBps"], "avg_launch_ms": stats["norm_kernel_ms"],
+                        "bytes_per_launch": stats["K"] * stats["P"] * (2 if stats["grad_dtype"] == "bf16" else 4),
+                        "frac": (stats["norm_kernel_GBps"] or 0.0) / HBM_PEAK_GBPS},
+        "whole_update": {"GBps": stats["GBps"], "frac": stats["frac_of_peak"], "ms_per_step": stats["ms_per_step"],
+                         "updates_per_s": stats["updates_per_s"], "bytes_per_update": stats["model_bytes"]},
+    }
+
+
+SWEEP_KEYS = ("workload", "variant", "ms_per_step", "updates_per_s", "GBps", "frac_of_peak", "pull_kernel_GBps",
+              "norm_kernel_GBps", "graph_replay_ms_per_step", "ms_per_step_event_pass")
 
 
 def main():
@@ -349,15 +395,6 @@ def main():
     torch.cuda.empty_cache()
     variant = pick_variant(w, a.variant)
 
-    roofline = {
-        "bound": "hbm", "kernel": "k_center_pull", "achieved": stats["pull_kernel_GBps"], "peak": HBM_PEAK_GBPS,
-        "unit": "GB/s", "frac": (stats["pull_kernel_GBps"] or 0.0) / HBM_PEAK_GBPS,
-        "traffic": measured_traffic(w.name, stats["variant"]),
-        "bytes_per_launch": stats["pull_kernel_bytes"], "avg_launch_ms": stats["pull_kernel_ms"],
-        "launch_ms": stats["pull_kernel_ms_spread"],
-        "norm_kernel": {"achieved": stats["norm_kernel_GBps"], "avg_launch_ms": stats["norm_kernel_ms"],
-                        "frac": (stats["norm_kernel_GBps"] or 0.0) / HBM_PEAK_GBPS},
-    }
     out = {
         "metric": "grawa_update_hbm_bandwidth", "value": stats["GBps"], "unit": "GB/s", "n_gpus": 1,
         "steps": a.steps, "warmup": a.warmup, "ms_per_step": stats["ms_per_step"], "higher_is_better": True,
@@ -368,31 +405,38 @@ def main():
         "frac_of_hbm_peak": stats["frac_of_peak"], "updates_per_s": stats["updates_per_s"],
         "device_ms_per_update": stats["device_ms"], "graph_replay_ms_per_step": stats["graph_replay_ms_per_step"],
         "ms_per_step_event_pass": stats["ms_per_step_event_pass"],
-        "roofline": roofline,
+        "roofline": roofline_of(stats),
     }
     out["copy_kernel"] = copy_ceiling(torch, grawa)
     out["frac_of_copy_kernel"] = stats["GBps"] / out["copy_kernel"]["GBps"]     # against this machine's own copy rate
     torch.cuda.empty_cache()
+    by_config = {w.name + "/" + stats["variant"]: roofline_of(stats)} if a.config in TARGET_CONFIGS else {}
     if not a.no_sweep:
         sweep = []
         for i in range(W.N_CONFIGS):
             if i == a.config:
-                sweep.append({k: stats[k] for k in ("workload", "variant", "ms_per_step", "updates_per_s", "GBps",
-                                                     "frac_of_peak", "pull_kernel_GBps", "norm_kernel_GBps",
-                                                     "graph_replay_ms_per_step", "ms_per_step_event_pass")})
+                sweep.append({k: stats[k] for k in SWEEP_KEYS})
                 continue
             for var in W.config(i).variants:
                 s, x, g, _ = time_config(torch, grawa, W, i, var, a.steps, a.warmup)
                 del x, g
                 torch.cuda.empty_cache()
-                sweep.append({k: s[k] for k in ("workload", "variant", "ms_per_step", "updates_per_s", "GBps",
-                                                 "frac_of_peak", "pull_kernel_GBps", "norm_kernel_GBps",
-                                                 "graph_replay_ms_per_step", "ms_per_step_event_pass")})
+                sweep.append({k: s[k] for k in SWEEP_KEYS})
+                if i in TARGET_CONFIGS and var == pick_variant(W.config(i), None):
+                    by_config[s["workload"] + "/" + s["variant"]] = roofline_of(s)
         out["all_configs"] = sweep
+        out["roofline_by_config"] = by_config
     if not a.no_phases and not a.no_sweep:
         out["phases"] = time_phases(torch, grawa, W, a.config, a.steps, a.warmup)
     if not a.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(torch, W, w, variant, a.cpu_seconds)
+        if not a.no_sweep:
+            cb = {w.name: out["cpu_baseline"]}
+            for i in TARGET_CONFIGS:
+                if i != a.config:
+                    wi = W.config(i)
+                    cb[wi.name] = cpu_baseline(torch, W, wi, pick_variant(wi, None), a.cpu_seconds)
+            out["cpu_baseline_by_config"] = cb
     print(json.dumps(out), flush=True)
 
 
