@@ -68,6 +68,10 @@ typedef enum {
 
 #define GRAWA_MAX_WORKERS 1024
 
+/* Bits of the plan's non-finite-score flag word (grawa_plan_nonfinite). */
+#define GRAWA_NONFINITE_LAYER_SCORE 1u /* a per-(worker, layer) score A_k^l of eq. (5)-(6), or a running estimate of it, was +inf or NaN */
+#define GRAWA_NONFINITE_MODEL_SCORE 2u /* a per-worker score A_k of eq. (2) or (3), or the sum of a worker's estimates, was +inf or NaN */
+
 typedef struct grawa_plan grawa_plan_t; /* opaque */
 
 /* Text for a status code (static storage, never NULL). */
@@ -133,6 +137,19 @@ grawa_status_t grawa_mgrawa_update(grawa_plan_t *plan, float *x, int64_t ldx, co
 grawa_status_t grawa_lgrawa_update(grawa_plan_t *plan, float *x, int64_t ldx, const void *g,
                                    int64_t ldg, grawa_dtype_t g_dtype, float lambda,
                                    float *center_out, float *weights_out, void *stream);
+
+/*
+ * Non-finite scores.  The paper does not say what a worker with an infinite or
+ * undefined gradient norm should get; by the weight formula a +inf score gives
+ * weight 0 and a NaN score makes its whole group of weights NaN (see above).
+ * Every call that turns scores into weights (the update calls, grawa_grad_norms,
+ * the Local-GRAWA communication) also records the event in a flag word in the
+ * plan's device workspace: GRAWA_NONFINITE_* bits, set on the device, sticky.
+ * grawa_plan_nonfinite waits for `stream`, copies the word to *flags_host (host
+ * pointer) and, if clear != 0, enqueues a kernel on `stream` that zeroes it.  It
+ * synchronises, so it is a polling call for the host, not for a captured graph.
+ */
+grawa_status_t grawa_plan_nonfinite(grawa_plan_t *plan, unsigned *flags_host, int clear, void *stream);
 
 /*
  * Center and pull with weights supplied by the caller (the display after eq. (2);

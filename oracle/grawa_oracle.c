@@ -273,3 +273,13 @@ int64_t oracle_leader(const double *loss, int64_t K)
         if (loss[m] < loss[best]) best = m;
     return best;
 }
+
+/* Whether any of n scores is +inf, -inf or NaN (the paper leaves such scores undefined; the
+ * update treats them by the weight formula and the library reports that it saw one). */
+int oracle_nonfinite(const double *A, int64_t n)
+{
+    if (!A || n < 0) return -1;
+    for (int64_t i = 0; i < n; ++i)
+        if (!isfinite(A[i])) return 1;
+    return 0;
+}

@@ -74,6 +74,8 @@ def _bind(L):
     L.oracle_easgd_center.restype = it
     L.oracle_leader.argtypes = [vp, i64]
     L.oracle_leader.restype = i64
+    L.oracle_nonfinite.argtypes = [vp, i64]
+    L.oracle_nonfinite.restype = it
     for name in ("oracle_norm_momentum", "oracle_sum_layers", "oracle_sumsq", "oracle_layer_norms", "oracle_model_norms", "oracle_weights",
                  "oracle_load_params", "oracle_local_sgd", "oracle_center", "oracle_pull",
                  "oracle_prox"):
@@ -156,6 +158,15 @@ def weights(A, *, _lib=None) -> np.ndarray:
     B = np.empty_like(A2)
     _ok((_lib or lib()).oracle_weights(_p(A2), A2.shape[0], A2.shape[1], _p(B)), "weights")
     return B.reshape(shape)
+
+
+def nonfinite(A, *, _lib=None) -> bool:
+    """True if any score in A is infinite or NaN."""
+    A = np.ascontiguousarray(A, dtype=np.float64)
+    rc = (_lib or lib()).oracle_nonfinite(_p(A), A.size)
+    if rc < 0:
+        raise ValueError("oracle nonfinite rejected its arguments")
+    return bool(rc)
 
 
 def update_chunks(x, beta, off, lam, *, g_sgd=None, lr=0.0, prox_center=None, mu=0.0, tau=1.0,

@@ -189,6 +189,7 @@ static grawa_status_t plan_create_impl(grawa_plan_t **out, int K, int64_t P, int
     p->d_beta_model = reinterpret_cast<float *>(w); w += b_bm;
     p->d_mvg = reinterpret_cast<double *>(w); w += b_mvg;
     p->d_local_t = reinterpret_cast<int64_t *>(w);
+    p->d_flags = reinterpret_cast<unsigned *>(w + 64);
 
     if (hipMemcpy(p->d_off, off, sizeof(int64_t) * ((size_t)L + 1), hipMemcpyHostToDevice) != hipSuccess ||
         hipMemcpy(p->d_cell_layer, m.cell_layer.data(), sizeof(int32_t) * (size_t)nc, hipMemcpyHostToDevice) != hipSuccess ||
@@ -445,6 +446,18 @@ grawa_status_t grawa_local_scores_reset(grawa_plan_t *p, void *stream)
     GRAWA_TRY_HIP(grawa_launch_zero_estimate(p, static_cast<hipStream_t>(stream)));
     p->local_t = 0;
     p->local_gamma = 0.0;
+    return GRAWA_OK;
+}
+
+grawa_status_t grawa_plan_nonfinite(grawa_plan_t *p, unsigned *flags_host, int clear, void *stream)
+{
+    if (!p || !flags_host) return GRAWA_ERR_INVALID_ARG;
+    DeviceGuard guard(p->device);
+    if (!guard.ok) return GRAWA_ERR_HIP;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    GRAWA_TRY_HIP(hipStreamSynchronize(s));
+    GRAWA_TRY_HIP(hipMemcpy(flags_host, p->d_flags, sizeof(unsigned), hipMemcpyDeviceToHost));
+    if (clear) GRAWA_TRY_HIP(grawa_launch_clear_flags(p, s));
     return GRAWA_OK;
 }
 

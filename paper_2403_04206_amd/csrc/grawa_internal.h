@@ -39,6 +39,7 @@ struct grawa_plan {
     float *d_beta_model;    // [K] model-level weights
     double *d_mvg;          // [K][L] moving average of the layer norms (running estimate, Appendix G)
     int64_t *d_local_t;     // device: local steps since the last communication (what the kernels use)
+    unsigned *d_flags;      // device: GRAWA_NONFINITE_* bits, sticky until read-and-cleared (may be null)
     int64_t local_t;        // host mirror of the counter as of the last enqueued call (argument checks only)
     double local_gamma;     // momentum of the running estimate used so far (0 = none yet)
     // measurement aid
@@ -89,6 +90,7 @@ hipError_t grawa_launch_finalize_layers(const grawa_plan *p, float *norms_user, 
 hipError_t grawa_launch_local_weights(const grawa_plan *p, double gamma, int per_layer, float *beta_user,
                                       float *est_user, hipStream_t s);
 hipError_t grawa_launch_zero_estimate(const grawa_plan *p, hipStream_t s);
+hipError_t grawa_launch_clear_flags(const grawa_plan *p, hipStream_t s);
 hipError_t grawa_launch_row_step(float *x, int64_t ldx, const void *g, int64_t ldg, grawa_dtype_t dt, float lr,
                                  const float *center, float w, int K, int64_t P, const GrawaTile *tiles,
                                  const int32_t *block_tile0, int64_t n_tiles, double *partials, hipStream_t s);

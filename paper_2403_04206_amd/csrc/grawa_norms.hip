@@ -100,18 +100,21 @@ __global__ __launch_bounds__(GRAWA_BLOCK) __attribute__((amdgpu_waves_per_eu(1, 
 // 1/A_k, summing to one, evaluated as (A_min/A_k) / sum_j (A_min/A_j) so that nothing
 // overflows.  Scores of exactly zero share the weight equally and take all of it (the
 // limit A -> 0+).  Called by ONE full wave (all 64 lanes); lanes stride over the workers.
+// A score that is +inf or NaN sets `bit` in the plan's flag word (flags may be null).
 __device__ __forceinline__ void group_weights(const double *sA, int K, float *beta, int64_t stride,
-                                              float *beta_user)
+                                              float *beta_user, unsigned *flags, unsigned bit)
 {
     const int lane = threadIdx.x & (GRAWA_WAVE - 1);
-    double mn = INFINITY, nz = 0.0;
+    double mn = INFINITY, nz = 0.0, bad = 0.0;
     for (int k = lane; k < K; k += GRAWA_WAVE) {
         const double a = sA[k];
         mn = fmin(mn, a);
         nz += (a == 0.0) ? 1.0 : 0.0;
+        bad += isfinite(a) ? 0.0 : 1.0;
     }
     const double a_min = wave_min(mn);
     const double n_zero = wave_sum(nz);
+    if (flags && wave_sum(bad) > 0.0 && lane == 0) atomicOr(flags, bit);
     double z = 0.0;
     if (n_zero == 0.0)
         for (int k = lane; k < K; k += GRAWA_WAVE) z += a_min / sA[k];
@@ -153,7 +156,7 @@ __global__ __launch_bounds__(GRAWA_FIN_BLOCK) void k_finalize_layers(
     const double *__restrict__ partials, int64_t n_tiles, const int32_t *__restrict__ layer_tile0,
     int K, int L, double *__restrict__ S, float *__restrict__ A, float *__restrict__ A_user,
     float *__restrict__ beta, float *__restrict__ beta_user, double *__restrict__ mvg, double gamma,
-    int64_t *__restrict__ local_t)
+    int64_t *__restrict__ local_t, unsigned *__restrict__ flags)
 {
     __shared__ double sA[GRAWA_MAX_WORKERS];
     __shared__ double sw[GRAWA_FIN_WAVES];
@@ -198,7 +201,7 @@ __global__ __launch_bounds__(GRAWA_FIN_BLOCK) void k_finalize_layers(
         if (mvg) mvg[(int64_t)k * L + l] = gamma * mvg[(int64_t)k * L + l] + (1.0 - gamma) * a;
     }
     __syncthreads();
-    if (wave == 0) group_weights(sA, K, beta + l, L, beta_user ? beta_user + l : nullptr);
+    if (wave == 0) group_weights(sA, K, beta + l, L, beta_user ? beta_user + l : nullptr, flags, GRAWA_NONFINITE_LAYER_SCORE);
 }
 
 // Weights from the running norm estimate g_est = gamma g_mvg / (1 - gamma^t) (Appendix G), t =
@@ -212,7 +215,8 @@ __global__ __launch_bounds__(GRAWA_FIN_BLOCK) void k_local_weights(const double 
                                                                    int K, int L, int per_layer,
                                                                    float *__restrict__ beta,
                                                                    float *__restrict__ beta_user,
-                                                                   float *__restrict__ est_user)
+                                                                   float *__restrict__ est_user,
+                                                                   unsigned *__restrict__ flags)
 {
     __shared__ double sA[GRAWA_MAX_WORKERS];
     const int lane = threadIdx.x & (GRAWA_WAVE - 1);
@@ -227,7 +231,8 @@ __global__ __launch_bounds__(GRAWA_FIN_BLOCK) void k_local_weights(const double 
             if (est_user) est_user[(int64_t)k * L + l] = (float)e;
         }
         __syncthreads();
-        if (wave == 0) group_weights(sA, K, beta + l, L, beta_user ? beta_user + l : nullptr);
+        if (wave == 0)
+            group_weights(sA, K, beta + l, L, beta_user ? beta_user + l : nullptr, flags, GRAWA_NONFINITE_LAYER_SCORE);
     } else {
         for (int k = wave; k < K; k += GRAWA_FIN_WAVES) {
             double s = 0.0;
@@ -240,7 +245,7 @@ __global__ __launch_bounds__(GRAWA_FIN_BLOCK) void k_local_weights(const double 
             if (lane == 0) sA[k] = s;
         }
         __syncthreads();
-        if (wave == 0) group_weights(sA, K, beta, 1, beta_user);
+        if (wave == 0) group_weights(sA, K, beta, 1, beta_user, flags, GRAWA_NONFINITE_MODEL_SCORE);
     }
 }
 
@@ -258,7 +263,8 @@ __global__ __launch_bounds__(GRAWA_BLOCK) void k_zero_estimate(double *__restric
 __global__ __launch_bounds__(GRAWA_FIN_BLOCK) void k_finalize_model(const double *__restrict__ S, int K,
                                                                     int L, int mode,
                                                                     float *__restrict__ beta,
-                                                                    float *__restrict__ beta_user)
+                                                                    float *__restrict__ beta_user,
+                                                                    unsigned *__restrict__ flags)
 {
     __shared__ double sA[GRAWA_MAX_WORKERS];
     const int lane = threadIdx.x & (GRAWA_WAVE - 1);
@@ -275,7 +281,13 @@ __global__ __launch_bounds__(GRAWA_FIN_BLOCK) void k_finalize_model(const double
         if (lane == 0) sA[k] = s;
     }
     __syncthreads();
-    if (wave == 0) group_weights(sA, K, beta, 1, beta_user);
+    if (wave == 0) group_weights(sA, K, beta, 1, beta_user, flags, GRAWA_NONFINITE_MODEL_SCORE);
+}
+
+// flag word <- 0
+__global__ void k_clear_flags(unsigned *__restrict__ flags)
+{
+    if (blockIdx.x == 0 && threadIdx.x == 0) *flags = 0u;
 }
 
 // Weights of the competing centers of Appendix F, written where the pull kernel reads its
@@ -327,7 +339,7 @@ hipError_t grawa_launch_finalize_layers(const grawa_plan *p, float *norms_user, 
     k_finalize_layers<<<dim3((unsigned)p->L), dim3(GRAWA_FIN_BLOCK), 0, s>>>(
         p->d_partials, update_estimate ? p->n_rtiles : p->n_tiles,
         update_estimate ? p->d_layer_rtile0 : p->d_layer_tile0, p->K, p->L, p->d_S, p->d_A, norms_user,
-        p->d_beta_layer, beta_user, update_estimate ? p->d_mvg : nullptr, gamma, p->d_local_t);
+        p->d_beta_layer, beta_user, update_estimate ? p->d_mvg : nullptr, gamma, p->d_local_t, p->d_flags);
     return hipGetLastError();
 }
 
@@ -336,7 +348,7 @@ hipError_t grawa_launch_local_weights(const grawa_plan *p, double gamma, int per
 {
     k_local_weights<<<dim3(per_layer ? (unsigned)p->L : 1u), dim3(GRAWA_FIN_BLOCK), 0, s>>>(
         p->d_mvg, gamma, p->d_local_t, p->K, p->L, per_layer, per_layer ? p->d_beta_layer : p->d_beta_model,
-        beta_user, est_user);
+        beta_user, est_user, p->d_flags);
     return hipGetLastError();
 }
 
@@ -352,7 +364,13 @@ hipError_t grawa_launch_finalize_model(const grawa_plan *p, grawa_norm_mode_t mo
                                        hipStream_t s)
 {
     k_finalize_model<<<dim3(1), dim3(GRAWA_FIN_BLOCK), 0, s>>>(p->d_S, p->K, p->L, (int)mode,
-                                                          p->d_beta_model, beta_user);
+                                                          p->d_beta_model, beta_user, p->d_flags);
+    return hipGetLastError();
+}
+
+hipError_t grawa_launch_clear_flags(const grawa_plan *p, hipStream_t s)
+{
+    k_clear_flags<<<dim3(1), dim3(GRAWA_WAVE), 0, s>>>(p->d_flags);
     return hipGetLastError();
 }
 

@@ -19,6 +19,7 @@ LIB_PATH = os.path.join(_PKG, "libgrawa.so")
 OK, ERR_INVALID_ARG, ERR_ALIGNMENT, ERR_WORKSPACE, ERR_UNSUPPORTED, ERR_HIP = range(6)
 F32, BF16 = 0, 1
 NORM_LAYERSUM, NORM_FLAT = 0, 1
+NONFINITE_LAYER_SCORE, NONFINITE_MODEL_SCORE = 1, 2
 MAX_WORKERS = 1024
 
 _NORM_MODES = {"layersum": NORM_LAYERSUM, "flat": NORM_FLAT, NORM_LAYERSUM: NORM_LAYERSUM, NORM_FLAT: NORM_FLAT}
@@ -65,6 +66,7 @@ def lib():
         "grawa_easgd_update": (it, [vp, vp, i64, fl, fl, vp, vp]),
         "grawa_lsgd_update": (it, [vp, vp, i64, vp, fl, vp, vp, vp]),
         "grawa_lgrawa_update_static": (it, [it, i64, it, vp, vp, i64, vp, i64, it, fl, vp, vp, vp]),
+        "grawa_plan_nonfinite": (it, [vp, C.POINTER(C.c_uint), it, vp]),
         "grawa_plan_profile": (it, [vp, it]),
         "grawa_plan_profile_read": (it, [vp, C.POINTER(it), C.POINTER(dbl), C.POINTER(dbl)]),
         "grawa_plan_profile_read_call": (it, [vp, it, C.POINTER(dbl), C.POINTER(dbl), C.POINTER(dbl)]),
@@ -313,6 +315,13 @@ class Plan:
                                        _vector(center_out, self.P, "center_out"),
                                        _vector(leader_out, 1, "leader_out", dtype=torch.int32), _stream(stream)),
                "grawa_lsgd_update")
+
+    def nonfinite(self, clear=True, stream=None):
+        """grawa_plan_nonfinite: the NONFINITE_* bits seen since the last clear (waits for the stream)."""
+        f = C.c_uint()
+        _check(lib().grawa_plan_nonfinite(self._h, C.byref(f), 1 if clear else 0, _stream(stream)),
+               "grawa_plan_nonfinite")
+        return f.value
 
     # -- measurement aid ------------------------------------------------------------
     def profile(self, enable: bool):

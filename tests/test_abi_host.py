@@ -87,6 +87,7 @@ def test_null_plan_and_null_buffers_are_rejected(L):
     assert L.grawa_center_pull(z, z, 16, z, 0, 0.1, z, z) == grawa.ERR_INVALID_ARG
     assert L.grawa_plan_profile(z, 1) == grawa.ERR_INVALID_ARG
     assert L.grawa_plan_info(z, None, None) == grawa.ERR_INVALID_ARG
+    assert L.grawa_plan_nonfinite(z, C.byref(C.c_uint()), 0, z) == grawa.ERR_INVALID_ARG
 
 
 def test_local_sgd_argument_checks(L):

@@ -63,9 +63,12 @@ def test_nesterov_reductions_and_errors():
         with pytest.raises(grawa.GrawaError) as e:
             grawa.local_nesterov(xa[:, :P], g[:, :P], buf[:, :P], 0.1, mom, wd)
         assert e.value.status == grawa.ERR_INVALID_ARG
-    with pytest.raises(grawa.GrawaError) as e:                               # buffer rows shorter than P
-        grawa.local_nesterov(xa[:, :P], g[:, :P], buf[:, :P - 4].contiguous(), 0.1, 0.9, 0.0)
-    assert e.value.status == grawa.ERR_INVALID_ARG
+    short = buf[:, :P - 4].contiguous()                                      # buffer rows shorter than P
+    with pytest.raises(ValueError):                                          # the binding refuses it ...
+        grawa.local_nesterov(xa[:, :P], g[:, :P], short, 0.1, 0.9, 0.0)
+    st = grawa.lib().grawa_local_nesterov(xa.data_ptr(), xa.stride(0), g.data_ptr(), g.stride(0), 0, short.data_ptr(),
+                                          short.stride(0), 3, P, 0.1, 0.9, 0.0, None)
+    assert st in (grawa.ERR_INVALID_ARG, grawa.ERR_ALIGNMENT)              # ... and so does the library (ldb < P)
 
 
 @pytest.mark.parametrize("K", [1, 4, 7, 16, 33, 70])
@@ -101,8 +104,10 @@ def test_easgd_limits():
             with pytest.raises(grawa.GrawaError) as e:
                 plan.easgd_update(x[:, :P], 0.3, rho, cen)
             assert e.value.status == grawa.ERR_INVALID_ARG
-        with pytest.raises(grawa.GrawaError):
+        with pytest.raises(TypeError):                      # the center is required (binding) ...
             plan.easgd_update(x[:, :P], 0.3, 0.5, None)
+        assert grawa.lib().grawa_easgd_update(plan._h, x.data_ptr(), x.stride(0), 0.3, 0.5, None, None) == \
+            grawa.ERR_INVALID_ARG                           # ... and by the library
         plan.easgd_update(x[:, :P], 0.0, 0.0, cen)          # rho = 0 keeps the center, lambda = 0 the workers
         torch.cuda.synchronize()
         assert torch.equal(cen, c0) and torch.equal(x, x0)

@@ -195,8 +195,14 @@ def test_non_finite_scores():
     wts = torch.empty((4, 4), device=DEV)
     xg = x.clone()
     with grawa.Plan(4, P, off) as plan:
+        assert plan.nonfinite() == 0
         plan.lgrawa_update(xg[:, :P], g[:, :P], 0.5, weights_out=wts)
         torch.cuda.synchronize()
+        # the flag word reports what the reference reports, and is sticky until cleared
+        assert orc.nonfinite(ref["norms"])
+        assert plan.nonfinite(clear=False) == grawa.NONFINITE_LAYER_SCORE
+        assert plan.nonfinite() == grawa.NONFINITE_LAYER_SCORE
+        assert plan.nonfinite() == 0
         got_b = wts.cpu().numpy()
         np.testing.assert_array_equal(np.isnan(got_b), np.isnan(ref["beta"]))
         assert_table_close(got_b[:, :3], ref["beta"][:, :3], TIGHT, "beta with an infinite score")
@@ -212,6 +218,12 @@ def test_non_finite_scores():
         torch.cuda.synchronize()
         refm = orc.mgrawa_update(xh, W.to_numpy_grads(g), off, 0.5)
         assert refm["beta"][1] == 0.0
+        assert orc.nonfinite(refm["norms"])
+        assert plan.nonfinite() == grawa.NONFINITE_LAYER_SCORE | grawa.NONFINITE_MODEL_SCORE
+        g[1, off[1] + 5] = 1.0                                  # all finite again: nothing is flagged
+        plan.mgrawa_update(x.clone()[:, :P], g[:, :P], 0.5)
+        plan.grad_norms(g[:, :P])
+        assert plan.nonfinite() == 0
         assert_table_close(wm.cpu().numpy(), refm["beta"], TIGHT, "model-level beta with an infinite score")
         assert_params_close(xg.cpu().numpy()[:, :P], refm["x"], off, TIGHT, "x, infinite score", operand_scale(xh[:, :P]))
 

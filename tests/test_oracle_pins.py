@@ -649,3 +649,15 @@ def test_lsgd_leader_and_pull():
     np.testing.assert_array_equal(cr, x[1].astype(np.float64))
     np.testing.assert_allclose(xn, xr, rtol=1e-15)
     np.testing.assert_array_equal(xn[1], x[1].astype(np.float64))   # the leader does not move
+
+
+def test_nonfinite_scores_are_reported():
+    # pinned to the IEEE classification numpy applies, on every special value and both signs
+    assert not orc.nonfinite(np.array([0.0, 1.0, 1e308, 5e-324, -2.5]))
+    assert not orc.nonfinite(np.zeros((3, 4)))
+    for bad in (np.inf, -np.inf, np.nan):
+        for pos in (0, 5, 11):
+            A = np.arange(12, dtype=np.float64).reshape(3, 4)
+            A.flat[pos] = bad
+            assert orc.nonfinite(A) and not np.isfinite(A).all()
+    assert not orc.nonfinite(np.array([]))
