@@ -20,47 +20,57 @@ __device__ __forceinline__ int layer_of(const int64_t *__restrict__ off, int lay
     return layer;
 }
 
-// grid ceil(P/256), block 256.  Lane t of block m owns column i = 256 m + t: it loads
-// x[k][i] for all K workers (K independent loads in flight; with SGD also g[k][i] and applies
-// x - lr g), forms c = sum_k beta_k x_k and writes x_k + lambda (c - x_k) back, so every
-// parameter is read once and written once.  A wave touches one 256-byte piece per row.
-// KT = number of register slots; EXACT says K == KT (no per-row guards, the usual case),
-// otherwise K <= KT.  NT = streaming loads/stores, chosen by the host only when every row
+// grid ceil(P/C), block S*C.  Thread t of block m owns column i = C m + (t mod C) and the rows of
+// row group t / C: it loads x[k][i] for its KT/S workers (all loads in flight together; with SGD
+// also g[k][i] and applies x - lr g), forms its part of c = sum_k beta_k x_k, the S parts are added
+// through LDS, and it writes x_k + lambda (c - x_k) back, so every parameter is read once and written
+// once.  A wave touches one 256-byte piece per row.  S = 1, C = 256 is the plain form (one lane owns a
+// whole column, no LDS, no barrier).
+// KT = number of register slots per column; EXACT says K == KT (no per-row guards, the usual case),
+// otherwise K <= KT (S = 1 only).  NT = streaming loads/stores, chosen by the host only when every row
 // starts on a 128-byte boundary.  Row bases are wave-uniform, the lane adds only its index.
-// cell_layer[m] >= 0: the whole block lies in that layer (weights come through scalar
-// loads); < 0: the block contains a layer boundary, ~cell_layer[m] is the layer of its first
-// column and each lane finds its own layer.  Model-level weights pass cell_layer = nullptr.
+// cell_layer[j] describes the 256-column cell j: >= 0: the whole cell lies in that layer (weights
+// come through scalar loads); < 0: the cell contains a layer boundary, ~cell_layer[j] is the layer of
+// its first column and each lane finds its own layer.  Model-level weights pass cell_layer = nullptr.
 // The pull is x + lambda (c - x), one fma, which leaves a single worker exactly unchanged.
 // moving != 0 (EASGD, Appendix F): center_out holds the previous center c0 on entry and the
 // center used and stored is c0 + rho (c - c0).
-// WPE caps the waves per SIMD: the pass is fastest with roughly 32-48 row loads in flight per
+// WPE caps the waves per SIMD: the plain form is fastest with roughly 32-48 row loads in flight per
 // SIMD (K x WPE); more only queues requests to K far-apart rows and costs DRAM efficiency
 // (measured: K = 16 at 3 waves 6.1 TB/s, at 8 waves 5.7; K = 8 at 4 waves 6.5, at 8 waves 6.2).
-template <int KT, bool EXACT, bool SGD, typename GT, bool NT, int WPE>
-__global__ __launch_bounds__(GRAWA_CELL) __attribute__((amdgpu_waves_per_eu(1, WPE))) void k_center_pull(
+// Splitting the rows over S groups of waves (3-4 rows per wave, the whole block starting its loads
+// and, after the barrier, its stores together) measured 2-4 % faster than the plain form for 12 and
+// 16 workers (with and without the SGD step); for every other worker count tried (6 to 32) the
+// plain form at its best occupancy cap is as fast or faster.
+template <int KT, bool EXACT, bool SGD, typename GT, bool NT, int WPE, int S, int C>
+__global__ __launch_bounds__(S *C) __attribute__((amdgpu_waves_per_eu(1, WPE))) void k_center_pull(
     float *__restrict__ x, int64_t ldx, const GT *__restrict__ g, int64_t ldg, float lr,
     const float *__restrict__ beta, int64_t beta_stride, const int32_t *__restrict__ cell_layer,
     const int64_t *__restrict__ off, int L, int K, int64_t P, float lambda,
     float *__restrict__ center_out, float rho, int moving)
 {
-    const int64_t cell0 = (int64_t)blockIdx.x * GRAWA_CELL; // wave-uniform
-    const unsigned t = threadIdx.x;
-    const bool ok = cell0 + t < P;
-    float *xb = x + cell0;
-    const GT *gb = g + cell0;
-    const unsigned xoff = t * 4u, goff = t * (unsigned)sizeof(GT);
-    const int nk = EXACT ? KT : K;
+    static_assert(S == 1 || (EXACT && KT % S == 0), "row groups need an exact, evenly divided worker count");
+    static_assert(C % GRAWA_WAVE == 0 && GRAWA_CELL % C == 0, "a block covers whole waves inside one cell");
+    constexpr int KS = KT / S; // rows per thread
+    const int64_t cell0 = (int64_t)blockIdx.x * C; // wave-uniform
+    const unsigned col = S == 1 ? threadIdx.x : threadIdx.x % C;
+    const int k0 = S == 1 ? 0 : __builtin_amdgcn_readfirstlane((int)(threadIdx.x / C) * KS); // wave-uniform
+    const bool ok = cell0 + col < P;
+    float *xb = x + cell0 + (int64_t)k0 * ldx;
+    const GT *gb = g + cell0 + (int64_t)k0 * ldg;
+    const unsigned xoff = col * 4u, goff = col * (unsigned)sizeof(GT);
+    const int nk = EXACT ? KS : K;
 
-    float v[KT];
+    float v[KS];
 #pragma unroll
-    for (int k = 0; k < KT; ++k) v[k] = 0.f;
+    for (int k = 0; k < KS; ++k) v[k] = 0.f;
     if (ok) {
 #pragma unroll
-        for (int k = 0; k < KT; ++k)
+        for (int k = 0; k < KS; ++k)
             if (k < nk) v[k] = ld_lane<NT, float>(uniform_base(xb + (int64_t)k * ldx), xoff);
         if (SGD) {
 #pragma unroll
-            for (int k = 0; k < KT; ++k)
+            for (int k = 0; k < KS; ++k)
                 if (k < nk)
                     v[k] = fmaf(-lr, Grad<GT>::template lane<NT>(uniform_base(gb + (int64_t)k * ldg), goff), v[k]);
         }
@@ -68,26 +78,34 @@ __global__ __launch_bounds__(GRAWA_CELL) __attribute__((amdgpu_waves_per_eu(1, W
     float cprev = 0.f;
     if (moving && ok) cprev = ld_lane<NT, float>(uniform_base(center_out + cell0), xoff);
 
-    const int info = cell_layer ? cell_layer[blockIdx.x] : 0;
+    const int info = cell_layer ? cell_layer[cell0 / GRAWA_CELL] : 0;
     float c = 0.f;
-    if (info >= 0) { // one layer for the whole block: weights through scalar loads
-        const uint64_t bb = uniform_base(beta + info);
+    if (info >= 0) { // one layer for the whole cell: weights through scalar loads
+        const uint64_t bb = uniform_base(beta + info + (int64_t)k0 * beta_stride);
 #pragma unroll
-        for (int k = 0; k < KT; ++k)
+        for (int k = 0; k < KS; ++k)
             if (k < nk) c = fmaf(ld_uniform_f32(bb, (int64_t)k * beta_stride), v[k], c);
-    } else if (ok) { // the block holds a layer boundary: each lane looks up its own layer
-        const float *b = beta + layer_of(off, ~info, L, cell0 + t);
+    } else if (ok) { // the cell holds a layer boundary: each lane looks up its own layer
+        const float *b = beta + layer_of(off, ~info, L, cell0 + col) + (int64_t)k0 * beta_stride;
 #pragma unroll
-        for (int k = 0; k < KT; ++k)
+        for (int k = 0; k < KS; ++k)
             if (k < nk) c = fmaf(b[(int64_t)k * beta_stride], v[k], c);
+    }
+    if (S > 1) { // add the row groups' parts, in group order
+        __shared__ float part[S][C];
+        part[threadIdx.x / C][col] = c;
+        __syncthreads();
+        c = 0.f;
+#pragma unroll
+        for (int s = 0; s < S; ++s) c += part[s][col];
     }
     if (moving) c = fmaf(rho, c - cprev, cprev);
 
     if (ok) {
 #pragma unroll
-        for (int k = 0; k < KT; ++k)
+        for (int k = 0; k < KS; ++k)
             if (k < nk) st_lane<NT, float>(uniform_base(xb + (int64_t)k * ldx), xoff, fmaf(lambda, c - v[k], v[k]));
-        if (center_out) st_lane<NT, float>(uniform_base(center_out + cell0), xoff, c);
+        if (center_out && k0 == 0) st_lane<NT, float>(uniform_base(center_out + cell0), xoff, c);
     }
 }
 
@@ -133,17 +151,27 @@ __global__ __launch_bounds__(GRAWA_CELL) void k_center_pull_any(
 constexpr int grawa_waves_for(int k, bool sgd)
 {
     if (sgd) return k <= 2 ? 8 : k == 3 ? 6 : k <= 5 ? 5 : k <= 7 ? 4 : k <= 11 ? 3 : 2;
-    return k <= 4 ? 8 : k == 5 ? 6 : k <= 7 ? 5 : k <= 10 ? 4 : k <= 20 ? 3 : k <= 28 ? 2 : 1;
+    return k <= 4 ? 8 : k == 5 ? 6 : k <= 7 ? 5 : k <= 10 ? 4 : k <= 16 ? 3 : k <= 28 ? 2 : 1;
 }
+
+// Row groups S and columns per block C by worker count: the plain form except where the split form
+// measured faster (12 and 16 workers).
+template <int KT, bool SGD> struct CpShape { static constexpr int S = 1, C = GRAWA_CELL; };
+template <> struct CpShape<12, false> { static constexpr int S = 3, C = 256; };
+template <> struct CpShape<16, false> { static constexpr int S = 4, C = 256; };
+template <> struct CpShape<12, true> { static constexpr int S = 4, C = 256; };
+template <> struct CpShape<16, true> { static constexpr int S = 4, C = 256; };
 
 template <int KT, bool EXACT, bool SGD, typename GT, bool NT>
 static void launch_cp(const grawa_plan *p, float *x, int64_t ldx, const void *g, int64_t ldg, float lr,
                       const float *beta, int per_layer, float lambda, float *center_out, float rho, int moving,
                       hipStream_t s, hipEvent_t e0, hipEvent_t e1)
 {
-    hipExtLaunchKernelGGL((k_center_pull<KT, EXACT, SGD, GT, NT, grawa_waves_for(KT, SGD)>),
-                          dim3((unsigned)p->n_cells), dim3(GRAWA_CELL), 0, s, e0, e1, 0, x, ldx, (const GT *)g, ldg,
-                          lr, beta, per_layer ? (int64_t)p->L : (int64_t)1,
+    constexpr int S = EXACT ? CpShape<KT, SGD>::S : 1, C = EXACT ? CpShape<KT, SGD>::C : GRAWA_CELL;
+    constexpr int WPE = S == 1 ? grawa_waves_for(KT, SGD) : 8;
+    const unsigned grid = (unsigned)((p->P + C - 1) / C);
+    hipExtLaunchKernelGGL((k_center_pull<KT, EXACT, SGD, GT, NT, WPE, S, C>), dim3(grid), dim3(S * C), 0, s, e0, e1, 0,
+                          x, ldx, (const GT *)g, ldg, lr, beta, per_layer ? (int64_t)p->L : (int64_t)1,
                           per_layer ? (const int32_t *)p->d_cell_layer : (const int32_t *)nullptr,
                           (const int64_t *)p->d_off, p->L, p->K, p->P, lambda, center_out, rho, moving);
 }

@@ -83,11 +83,11 @@ RAGGED = [1, 3, 8193, 2, 5, 8191, 20000, 7, 1, 1, 4096, 33, 16385, 6]     # cros
 SMALL = [5, 1, 33, 8, 130]
 
 
-@pytest.mark.parametrize("K", [1, 2, 3, 4, 5, 8, 9, 16, 17, 32, 33, 40, 64, 65, 70])
+@pytest.mark.parametrize("K", [1, 2, 3, 4, 5, 8, 9, 12, 16, 17, 18, 20, 32, 33, 40, 64, 65, 70])
 @pytest.mark.parametrize("dtype", ["f32", "bf16"])
 @pytest.mark.parametrize("ld_pad", [0, 8])       # 0: cache-line aligned rows (streaming path); 8: not
 def test_worker_counts_ragged(K, dtype, ld_pad):
-    sizes = RAGGED if K <= 17 else RAGGED[:8]
+    sizes = RAGGED if K <= 20 else RAGGED[:8]
     w, x, g = W.make_small(100 + K, K, sizes, grad_dtype=dtype, ld_pad=ld_pad, device=DEV)
     say("ragged K=%d dtype=%s ld_pad=%d P=%d" % (K, dtype, ld_pad, w.P))
     for variant in ("mgrawa", "lgrawa"):
