@@ -440,7 +440,13 @@ def main():
                 if i == a.config and var == variant:
                     sweep.append({k: stats[k] for k in SWEEP_KEYS})
                     continue
-                s = time_config_in_child(i, var, a.steps, a.warmup)
+                try:
+                    s = time_config_in_child(i, var, a.steps, a.warmup)
+                except Exception as e:        # reported; the configuration is then timed in this process instead
+                    print("bench.py: %s; timing configuration %d here" % (e, i), file=sys.stderr)
+                    s, x, g, _ = time_config(torch, grawa, W, i, var, a.steps, a.warmup)
+                    del x, g
+                    torch.cuda.empty_cache()
                 sweep.append({k: s[k] for k in SWEEP_KEYS})
                 if i in TARGET_CONFIGS and var == pick_variant(W.config(i), None):
                     by_config[s["workload"] + "/" + s["variant"]] = roofline_of(s)
