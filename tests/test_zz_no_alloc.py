@@ -92,3 +92,33 @@ def test_static_limits_launch_nothing():
     assert f(2, big, 1, a, a, big, a, big, 0, 0.1, z, z, z) == grawa.ERR_UNSUPPORTED
     # and a worker count whose partial sums do not fit: K = 1024, 2^28 columns
     assert f(1024, 1 << 28, 1, a, a, 1 << 28, a, 1 << 28, 0, 0.1, z, z, z) == grawa.ERR_UNSUPPORTED
+
+
+def test_static_under_graph_capture():
+    # what the entry point is for: recorded into a HIP graph (after one eager call on the device, which looks
+    # up the array) and replayed, with eager work in between, it gives bit for bit what the plan-based call gives
+    w, x, g = W.make_small(830, 16, RAGGED, device=DEV)
+    P, K, L = w.P, w.K, w.L
+    say("static under graph capture K=%d P=%d" % (K, P))
+    off_dev = torch.from_numpy(w.offsets).to(DEV)
+    xs = x.clone()
+    cen_g, cen_e = torch.empty(W.round_up(P, 4), device=DEV), torch.empty(W.round_up(P, 4), device=DEV)
+    wts_g, wts_e = torch.empty((K, L), device=DEV), torch.empty((K, L), device=DEV)
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):                                       # warm-up outside the capture
+        grawa.lgrawa_update_static(xs[:, :P], g[:, :P], off_dev, 0.3)
+    torch.cuda.current_stream().wait_stream(side)
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        grawa.lgrawa_update_static(xs[:, :P], g[:, :P], off_dev, 0.3, center_out=cen_g, weights_out=wts_g)
+    with grawa.Plan(K, P, w.offsets) as plan:
+        for rep in range(3):
+            xe = x.clone() + rep
+            xs.copy_(xe)
+            plan.lgrawa_update(xe[:, :P], g[:, :P], 0.3, center_out=cen_e, weights_out=wts_e)
+            graph.replay()
+            torch.cuda.synchronize()
+            assert torch.equal(xs, xe), "replay %d differs" % rep
+            assert torch.equal(cen_g[:P], cen_e[:P]) and torch.equal(wts_g, wts_e)
