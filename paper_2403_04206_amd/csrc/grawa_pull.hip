@@ -146,12 +146,14 @@ __global__ __launch_bounds__(GRAWA_CELL) void k_center_pull_any(
 // launchers
 // ---------------------------------------------------------------------------------
 
-// Waves per SIMD the center+pull kernel is capped at, from a sweep of this kernel over K and
-// the cap on the part (best throughput at roughly 32-48 row loads in flight per SIMD).
+// Waves per SIMD the center+pull kernel is capped at, from sweeps of this kernel over K and
+// the cap on the part, on arrays of 3 to 11 GB (best throughput at roughly 24-48 row loads in
+// flight per SIMD; the larger the arrays, the lower the best cap: K = 8 on 11 GB runs 3 % faster
+// at 3 waves than at 4, on 3 GB equally fast).
 constexpr int grawa_waves_for(int k, bool sgd)
 {
-    if (sgd) return k <= 2 ? 8 : k == 3 ? 6 : k <= 5 ? 5 : k <= 7 ? 4 : k <= 11 ? 3 : 2;
-    return k <= 4 ? 8 : k == 5 ? 6 : k <= 7 ? 5 : k <= 10 ? 4 : k <= 16 ? 3 : k <= 28 ? 2 : 1;
+    if (sgd) return k <= 3 ? 8 : k == 4 ? 5 : k <= 7 ? 4 : k <= 11 ? 3 : 2;
+    return k <= 4 ? 8 : k == 5 ? 5 : k <= 7 ? 4 : k <= 16 ? 3 : k <= 28 ? 2 : 1;
 }
 
 // Row groups S and columns per block C by worker count: the plain form except where the split form
