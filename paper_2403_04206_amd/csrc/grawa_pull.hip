@@ -38,10 +38,10 @@ __device__ __forceinline__ int layer_of(const int64_t *__restrict__ off, int lay
 // WPE caps the waves per SIMD: the plain form is fastest with roughly 32-48 row loads in flight per
 // SIMD (K x WPE); more only queues requests to K far-apart rows and costs DRAM efficiency
 // (measured: K = 16 at 3 waves 6.1 TB/s, at 8 waves 5.7; K = 8 at 4 waves 6.5, at 8 waves 6.2).
-// Splitting the rows over S groups of waves (3-4 rows per wave, the whole block starting its loads
-// and, after the barrier, its stores together) measured 2-4 % faster than the plain form for 12 and
-// 16 workers (with and without the SGD step); for every other worker count tried (6 to 32) the
-// plain form at its best occupancy cap is as fast or faster.
+// Splitting the rows over S groups of waves (4 rows per wave, the whole block starting its loads
+// and, after the barrier, its stores together) measured 1-2 % faster than the plain form for 16
+// workers; for every other worker count tried (6 to 32, with and without the SGD step) the plain
+// form at its best occupancy cap is as fast or faster on arrays of random values.
 template <int KT, bool EXACT, bool SGD, typename GT, bool NT, int WPE, int S, int C>
 __global__ __launch_bounds__(S *C) __attribute__((amdgpu_waves_per_eu(1, WPE))) void k_center_pull(
     float *__restrict__ x, int64_t ldx, const GT *__restrict__ g, int64_t ldg, float lr,
@@ -147,22 +147,19 @@ __global__ __launch_bounds__(GRAWA_CELL) void k_center_pull_any(
 // ---------------------------------------------------------------------------------
 
 // Waves per SIMD the center+pull kernel is capped at, from sweeps of this kernel over K and
-// the cap on the part, on arrays of 3 to 11 GB (best throughput at roughly 24-48 row loads in
-// flight per SIMD; the larger the arrays, the lower the best cap: K = 8 on 11 GB runs 3 % faster
-// at 3 waves than at 4, on 3 GB equally fast).
+// the cap on the part, on arrays of 3 to 11 GB holding random values (best throughput at roughly
+// 24-48 row loads in flight per SIMD).  The values matter: arrays of zeros stream about 4 % faster
+// on this part and shift some of the optima, so sweeps over cleared memory mislead.
 constexpr int grawa_waves_for(int k, bool sgd)
 {
-    if (sgd) return k <= 3 ? 8 : k == 4 ? 5 : k <= 7 ? 4 : k <= 11 ? 3 : 2;
-    return k <= 4 ? 8 : k == 5 ? 5 : k <= 7 ? 4 : k <= 16 ? 3 : k <= 28 ? 2 : 1;
+    if (sgd) return k <= 3 ? 8 : k <= 5 ? 5 : k <= 7 ? 4 : k <= 11 ? 3 : 2;
+    return k <= 4 ? 8 : k == 5 ? 5 : k <= 8 ? 4 : k <= 16 ? 3 : k <= 28 ? 2 : 1;
 }
 
 // Row groups S and columns per block C by worker count: the plain form except where the split form
-// measured faster (12 and 16 workers).
+// measured faster on arrays of random values (16 workers without the SGD step).
 template <int KT, bool SGD> struct CpShape { static constexpr int S = 1, C = GRAWA_CELL; };
-template <> struct CpShape<12, false> { static constexpr int S = 3, C = 256; };
 template <> struct CpShape<16, false> { static constexpr int S = 4, C = 256; };
-template <> struct CpShape<12, true> { static constexpr int S = 4, C = 256; };
-template <> struct CpShape<16, true> { static constexpr int S = 4, C = 256; };
 
 template <int KT, bool EXACT, bool SGD, typename GT, bool NT>
 static void launch_cp(const grawa_plan *p, float *x, int64_t ldx, const void *g, int64_t ldg, float lr,
