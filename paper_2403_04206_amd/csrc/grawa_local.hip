@@ -219,9 +219,10 @@ __global__ __launch_bounds__(GRAWA_COPY_BLOCK) void k_stream_copy(v4u *__restric
 
 // center == nullptr: no proximity step.  partials == nullptr: no scores (tiles, block_tile0 and
 // n_tiles are then unused); otherwise they are the plan's 1024-column tile map, its index by
-// aligned block and its length.  Vector shapes: fp32 gradients V = 1, U = 4, with the proximity
-// step V = 4, U = 1; bf16 V = 2, U = 2 for the plain step, else V = 4, U = 1 (each the fastest
-// measured for its case; the spread between shapes is 3-10 %).
+// aligned block and its length.  Vector shapes: fp32 gradients V = 1, U = 4 for the plain step,
+// V = 4, U = 1 with the proximity step or the scores; bf16 V = 2, U = 2 for the plain step, else
+// V = 4, U = 1 (each the fastest measured for its case on arrays of random values; the spread
+// between shapes is 3-10 %).
 hipError_t grawa_launch_row_step(float *x, int64_t ldx, const void *g, int64_t ldg, grawa_dtype_t dt, float lr,
                                  const float *center, float w, int K, int64_t P, const GrawaTile *tiles,
                                  const int32_t *block_tile0, int64_t n_tiles, double *partials, hipStream_t s)
@@ -252,7 +253,7 @@ hipError_t grawa_launch_row_step(float *x, int64_t ldx, const void *g, int64_t l
     } else {
         if (prox && score) GRAWA_RS_NT(float, 4, 1, true, true);
         else if (prox) GRAWA_RS_NT(float, 4, 1, true, false);
-        else if (score) GRAWA_RS_NT(float, 1, 4, false, true);
+        else if (score) GRAWA_RS_NT(float, 4, 1, false, true);
         else GRAWA_RS_NT(float, 1, 4, false, false);
     }
 #undef GRAWA_RS_NT

@@ -65,9 +65,9 @@ def test_static_layouts(K, sizes):
 
 
 def test_static_benchmark_size():
-    # configuration 2 (K = 16, 36.5 M parameters, 80 ragged layers): the streaming path, then the small
-    # configuration 0 right after it
-    for idx in (2, 0):
+    # configurations 3 (the largest: 354 M parameters, 7 MiB of the fixed workspace), 4 (K = 32, 161 layers),
+    # 2 (K = 16, 80 ragged layers) on the streaming path, then the small configuration 0 right after them
+    for idx in (3, 4, 2, 0):
         w = W.config(idx)
         say("static %s K=%d L=%d P=%d" % (w.name, w.K, w.L, w.P))
         x, g = W.make_inputs(w, device=DEV)
