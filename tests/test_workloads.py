@@ -59,3 +59,17 @@ def test_inputs_are_seeded_and_shaped():
     # the configuration with one tiny-gradient worker
     w4 = W.config(4)
     assert w4.tiny_worker == 0 and np.all(W.grad_scales(w4)[0] == 1e-6) and w4.fused_sgd
+
+
+def test_explicit_scale_table_is_honoured():
+    # the extreme-magnitude parity cases put chosen standard deviations on chosen (worker, layer) blocks
+    table = np.array([[1e-30, 1e20, 1.0], [3e-30, 1e-21, 0.1]])
+    w = W.Workload("explicit", 2, [5000, 3000, 4000], scale_table=table, seed=(9, 9))
+    assert np.array_equal(W.grad_scales(w), table)
+    _, g = W.make_inputs(w)
+    for k in range(2):
+        for l in range(3):
+            blk = g[k, int(w.offsets[l]):int(w.offsets[l + 1])].double()
+            assert 0.9 < float(blk.std()) / table[k, l] < 1.1
+    with np.testing.assert_raises(ValueError):
+        W.grad_scales(W.Workload("bad", 2, [10, 10], scale_table=np.ones((3, 2))))
