@@ -53,6 +53,8 @@ MUTANTS = [
     ("easgd_sum_not_mean", "rho * (s / (double)K);", "rho * s;"),
     ("leader_is_largest_loss", "if (loss[m] < loss[best]) best = m;", "if (loss[m] > loss[best]) best = m;"),
     ("leader_last_on_ties", "if (loss[m] < loss[best]) best = m;", "if (loss[m] <= loss[best]) best = m;"),
+    ("nonfinite_misses_infinity", "if (!isfinite(A[i])) return 1;", "if (isnan(A[i])) return 1;"),
+    ("nonfinite_skips_last_entry", "for (int64_t i = 0; i < n; ++i)\n        if (!isfinite(A[i])) return 1;", "for (int64_t i = 0; i + 1 < n; ++i)\n        if (!isfinite(A[i])) return 1;"),
     ("layer_sum_skips_first", "for (int64_t k = 0; k < L; ++k) a += est[m * L + k];", "for (int64_t k = 1; k < L; ++k) a += est[m * L + k];"),
 ]
 
