@@ -41,11 +41,13 @@ def test_c_program_matches_the_reference():
     lines = res.stdout.split("\n")
     P, ld, x, g = lcg_inputs()
     assert lines[0] == "P %d ld %d" % (P, ld)
-    vals = {"beta_layer": [], "beta_model": [], "x": []}
+    vals = {"beta_layer": [], "beta_model": [], "x": [], "static_equal": [], "nonfinite": []}
     for ln in lines[1:]:
         if ln:
             name, v = ln.split()
             vals[name].append(float(v))
+    assert vals["static_equal"] == [1.0], "the allocation-free call differs from the plan-based one"
+    assert vals["nonfinite"] == [0.0]
     off = np.concatenate([[0], np.cumsum(SIZES)])
     # the same three calls through the reference, the state rounded to fp32 between calls as it is stored
     x1 = orc.local_sgd(x, g, 0.125, P=P).astype(np.float32)
